@@ -1,0 +1,190 @@
+/*
+ * flowcache.h -- C ABI of the FlowCache denoising-step hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the per-tick work that FlowCache
+ * ("Flow Caching for Autoregressive Video Generation") adds to, or keeps from, a causal
+ * diffusion-forcing video DiT layer:
+ *
+ *   flowcache_chunk_decide    per-chunk relative-L1 change metric, accumulate-and-threshold
+ *                             reuse decision and gather of the chunks to recompute
+ *                             (Sec. 3.2, Eq. (5) and Eq. (8)).
+ *   flowcache_attend          chunk-causal multi-head attention of the recompute chunks
+ *                             against [clean KV cache | active chunks' KV], optionally
+ *                             emitting the per-key attention mass (Sec. 3.3, Eq. (9)).
+ *   flowcache_attention_mass  the importance mass alone, for explicit observation queries
+ *                             (Sec. 3.3, Eq. (9); observation window of App. C.2).
+ *   flowcache_kv_compress     joint importance-redundancy scoring, per-head top-B selection
+ *                             and in-place compaction of K and V (Sec. 3.3, Eq. (10)-(12),
+ *                             linear-time redundancy of App. C.2, phases of App. C.1).
+ *
+ * Conventions common to all calls
+ * -------------------------------
+ *  - Pointers marked [dev] are DEVICE pointers owned by the caller; [host] are host
+ *    pointers read during the call only.  The library never allocates, frees or keeps a
+ *    pointer.  Scratch space is a caller-provided device workspace whose size comes from
+ *    the matching *_workspace() query (256-byte aligned; contents need no initialisation
+ *    and are undefined afterwards).
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *    stream) and the call returns without synchronising.  Calls that share a workspace
+ *    must be stream-ordered.
+ *  - Return value: FC_OK or an error code.  Argument errors are detected and returned
+ *    BEFORE any HIP call is made, so they can be exercised on a machine without a GPU.
+ *    No exception crosses the boundary; the library keeps no global state.
+ *  - dtype FC_F32: float tensors, fp32 arithmetic.  FC_BF16: bfloat16 tensors, bf16 x bf16
+ *    -> fp32 matrix-core products, fp32 softmax state, bf16 output.
+ *  - Decisions (reuse masks) and kept-token indices are taken in float64 and are meant to
+ *    be bit-reproducible run to run: no floating-point atomics are used anywhere.
+ */
+#ifndef FLOWCACHE_H
+#define FLOWCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FC_F32 = 0, FC_BF16 = 1 } fc_dtype;
+
+typedef void* fc_stream; /* hipStream_t */
+
+enum {
+    FC_OK = 0,
+    FC_INVALID_ARGUMENT = 1,    /* null pointer, negative size, eps < 0 or NaN, even pool width ... */
+    FC_UNSUPPORTED = 2,         /* shape/dtype outside what the kernels cover (e.g. head_dim)       */
+    FC_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below the *_workspace() figure                   */
+    FC_HIP_ERROR = 4            /* a HIP runtime call or kernel launch failed                       */
+};
+
+#define FC_MAX_ACTIVE 16 /* largest number of active chunks in the denoising window */
+
+/* Human-readable name of a status code (static storage). */
+const char* flowcache_status_string(int status);
+
+/* Library version, major*100 + minor. */
+int flowcache_version(void);
+
+/*
+ * Change metric, reuse decision and gather.  Sec. 3.2: Eq. (5) per chunk, then Eq. (8).
+ *
+ *   L1rel_i = sum|x_cur[i] - x_prev[i]| / sum|x_prev[i]|        (previous tick in the denominator;
+ *                                                                  zero denominator -> +inf)
+ *   step_idx[i] < warmup_m          : f_i = 0                    (first m local steps never reuse)
+ *   acc[i] + L1rel_i  > eps         : f_i = 0
+ *   otherwise                       : f_i = acc[i] + L1rel_i
+ *   recompute_i = (f_i == 0);  acc[i] <- f_i
+ *
+ * Elements are widened exactly to float64; sums and the comparison are float64.
+ *
+ *   x_cur, x_prev  [dev] [A, chunk_elems] contiguous, `dtype`
+ *   step_idx       [dev] [A] int32, steps already taken by each chunk
+ *   acc            [dev] [A] float64, in/out accumulator f
+ *   l1rel          [dev] [A] float64 out, may be NULL
+ *   recompute_mask [dev] [A] uint8 out, 1 = recompute
+ *   recompute_idx  [dev] [A] int32 out: ascending list of chunks to recompute in its first
+ *                        *n_recompute entries, the rest set to -1
+ *   n_recompute    [dev] [1] int32 out
+ *   x_compact      [dev] [A, chunk_elems] out, may be NULL: block r receives
+ *                        x_cur[recompute_idx[r]] for r < *n_recompute; other blocks untouched
+ * Errors: A outside [1, FC_MAX_ACTIVE], chunk_elems < 1, warmup_m < 0, eps < 0 or not
+ * finite, null pointers -> FC_INVALID_ARGUMENT.
+ */
+int flowcache_chunk_decide(const void* x_cur, const void* x_prev, fc_dtype dtype, int A,
+                           int64_t chunk_elems, const int32_t* step_idx, int warmup_m,
+                           double eps, double* acc, double* l1rel, uint8_t* recompute_mask,
+                           int32_t* recompute_idx, int32_t* n_recompute, void* x_compact,
+                           void* workspace, size_t workspace_bytes, fc_stream stream);
+size_t flowcache_chunk_decide_workspace(int A, int64_t chunk_elems);
+
+/*
+ * Chunk-causal attention of the recompute chunks.  Sec. 3.3 (clean chunks live in the KV
+ * cache and are attended by the chunks being denoised); softmax(q K^T * scale) V.
+ *
+ * A query of active chunk c sees cache positions [0, L_clean) and the slots of active
+ * chunks 0..c (its own chunk entirely: bidirectional inside a chunk, causal across chunks).
+ * Slots of chunks that are NOT recomputed this tick keep, and expose, their stale K/V.
+ *
+ *   q        [dev] [A*L_c, H_q, d] compact: row block r <-> chunk recompute_idx[r]
+ *   k_new,
+ *   v_new    [dev] [A*L_c, H_k, d] compact, same row blocks; may both be NULL when the
+ *                  caller has already written the slots.  Otherwise block r is first
+ *                  copied into slot active_off[recompute_idx[r]] of the caches.
+ *   k_cache,
+ *   v_cache  [dev] head-major: element (h, pos, e) at h*kv_head_stride + pos*kv_tok_stride + e
+ *                  (strides in elements; kv_tok_stride >= d and a multiple of 8,
+ *                  kv_head_stride >= capacity*kv_tok_stride)
+ *   capacity       number of token positions per head in the caches
+ *   active_off [host] [A] first cache position of each active chunk's slot, in causal
+ *                  order; slots are L_c long, lie in [L_clean, capacity] and do not overlap
+ *   recompute_idx, n_recompute [dev] as written by flowcache_chunk_decide
+ *   softmax_scale  0 selects d^-1/2
+ *   out      [dev] [A*L_c, H_q, d] `dtype`; only row blocks r < *n_recompute are written
+ *   lse      [dev] [H_q, A*L_c] float32 natural-log sum-exp of each row, may be NULL
+ *   mass     [dev] [H_k, mass_len] float32, may be NULL.  When given, receives Eq. (9)
+ *                  over cache positions [0, mass_len): the mean, over the last `obs_window`
+ *                  rows (0 = all L_c rows) of the LAST compact row block and over the
+ *                  H_q/H_k query heads of each key head, of softmax restricted to those
+ *                  positions.  That block must hold the last active chunk (A-1); if it
+ *                  does not, mass is filled with NaN.
+ * Supported: d in {64, 128}; H_q % H_k == 0; A <= FC_MAX_ACTIVE; FC_BF16 needs d == 128 or 64.
+ */
+int flowcache_attend(const void* q, const void* k_new, const void* v_new, void* k_cache,
+                     void* v_cache, int64_t kv_head_stride, int64_t kv_tok_stride,
+                     int capacity, fc_dtype dtype, int H_q, int H_k, int d, int L_c,
+                     int L_clean, int A, const int32_t* active_off,
+                     const int32_t* recompute_idx, const int32_t* n_recompute,
+                     float softmax_scale, void* out, float* lse, float* mass, int mass_len,
+                     int obs_window, void* workspace, size_t workspace_bytes,
+                     fc_stream stream);
+size_t flowcache_attend_workspace(int A, int L_c, int H_q, int H_k, int d, int mass_len,
+                                  int obs_window);
+
+/*
+ * Importance mass, Eq. (9), for explicit observation queries (App. C.2 uses the last 50
+ * query tokens of the last denoising chunk).
+ *
+ *   q_obs  [dev] [W, H_q, d] `dtype`
+ *   k_cache [dev] head-major as above; positions [0, mass_len) are scored
+ *   mass   [dev] [H_k, mass_len] float32 out; each row sums to 1
+ */
+int flowcache_attention_mass(const void* q_obs, int W, const void* k_cache,
+                             int64_t kv_head_stride, int64_t kv_tok_stride, fc_dtype dtype,
+                             int H_q, int H_k, int d, int mass_len, float softmax_scale,
+                             float* mass, void* workspace, size_t workspace_bytes,
+                             fc_stream stream);
+size_t flowcache_attention_mass_workspace(int W, int H_q, int H_k, int d, int mass_len);
+
+/*
+ * KV-cache compression at a chunk commit.  Sec. 3.3, per key head h over the first L_k
+ * cache positions (the merged set: clean region followed by the chunk that just finished):
+ *
+ *   Imp~_j  = max of mass over the window |u - j| <= pool_k/2                      Eq. (10)
+ *   k^_j    = k_j / max(||k_j||_2, 1e-12)
+ *   r_j     = (k^_j . sum_i k^_i  -  k^_j . k^_j) / L_k     linear form, App. C.2, of the
+ *                                                           diagonal-zeroed mean of Eq. (11)
+ *   Red_j   = softmax_j(r)                                                         Eq. (11)
+ *   Score_j = lambda * Imp~_j - (1 - lambda) * Red_j                               Eq. (12)
+ *
+ * The `budget` highest scores are kept (ties: lower position wins); the kept rows of K
+ * and V move, in ascending original position, to positions [0, budget) of the same buffers.
+ * Positions >= budget keep their old contents.  budget >= L_k is the cache-filling phase
+ * of App. C.1: kept_idx = 0..L_k-1 and the buffers are untouched.  All scoring arithmetic
+ * is float64.
+ *
+ *   mass     [dev] [H_k, L_k] float32, Eq. (9) importance before pooling
+ *   kept_idx [dev] [H_k, min(budget, L_k)] int32 out, ascending original positions
+ * Errors: pool_k even or < 1, lambda outside [0,1], budget < 1, L_k < 1 -> FC_INVALID_ARGUMENT;
+ * d not in {64, 128} -> FC_UNSUPPORTED.
+ */
+int flowcache_kv_compress(void* k_cache, void* v_cache, int64_t kv_head_stride,
+                          int64_t kv_tok_stride, fc_dtype dtype, int H_k, int d, int L_k,
+                          int budget, const float* mass, int pool_k, double lambda,
+                          int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                          fc_stream stream);
+size_t flowcache_kv_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLOWCACHE_H */

@@ -1,0 +1,228 @@
+// Change metric, reuse decision and gather (Sec. 3.2, Eq. (5) and Eq. (8)).
+//
+// Three stream-ordered kernels:
+//   1. decide_reduce   streaming pass over x_cur / x_prev: per block partial sums of
+//                      |x_cur - x_prev| and |x_prev| in float64 (HBM-bound, 16-byte loads,
+//                      contiguous segment per block, no atomics -> deterministic).
+//   2. decide_finalize one block: fixed-order sum of the partials, Eq. (8) per chunk,
+//                      ascending recompute list and count.
+//   3. gather_chunks   block copies x_cur[idx[r]] -> x_compact[r] for r < n_recompute
+//                      (the count is read on the device: no host round trip).
+#include "fc_common.hpp"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+template <typename T>
+__device__ __forceinline__ void accum_vec(const uint4& c, const uint4& p, double (&n)[4],
+                                          double (&d)[4]) {
+    float fc[Elem<T>::kVec], fp[Elem<T>::kVec];
+    unpack16(c, fc, T());
+    unpack16(p, fp, T());
+#pragma unroll
+    for (int e = 0; e < Elem<T>::kVec; ++e) {
+        const double a = (double)fc[e];
+        const double b = (double)fp[e];
+        n[e & 3] += fabs(a - b);
+        d[e & 3] += fabs(b);
+    }
+}
+
+template <typename T, bool VEC>
+__global__ __launch_bounds__(kThreads) void decide_reduce_kernel(
+    const T* __restrict__ x_cur, const T* __restrict__ x_prev, int64_t chunk_elems, int bpc,
+    double* __restrict__ partial) {
+    const int chunk = blockIdx.x / bpc;
+    const int bi = blockIdx.x % bpc;
+    const int tid = threadIdx.x;
+    const T* c = x_cur + (int64_t)chunk * chunk_elems;
+    const T* p = x_prev + (int64_t)chunk * chunk_elems;
+    double n[4] = {0.0, 0.0, 0.0, 0.0};
+    double d[4] = {0.0, 0.0, 0.0, 0.0};
+    if (VEC) {
+        constexpr int V = Elem<T>::kVec;
+        const int64_t nvec = chunk_elems / V;
+        const int64_t seg = (nvec + bpc - 1) / bpc;
+        const int64_t lo = (int64_t)bi * seg;
+        const int64_t hi = (lo + seg < nvec) ? lo + seg : nvec;
+        const uint4* c4 = reinterpret_cast<const uint4*>(c);
+        const uint4* p4 = reinterpret_cast<const uint4*>(p);
+        int64_t i = lo + tid;
+        for (; i + 3 * kThreads < hi; i += 4 * kThreads) {
+            uint4 cv[4], pv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                cv[u] = nt_load16(c4 + i + u * kThreads);
+                pv[u] = nt_load16(p4 + i + u * kThreads);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) accum_vec<T>(cv[u], pv[u], n, d);
+        }
+        for (; i < hi; i += kThreads) {
+            const uint4 cv = nt_load16(c4 + i);
+            const uint4 pv = nt_load16(p4 + i);
+            accum_vec<T>(cv, pv, n, d);
+        }
+        if (bi == 0) {  // elements past the last whole vector
+            const int64_t t = nvec * V + tid;
+            if (t < chunk_elems) {
+                const double a = (double)Elem<T>::to_f32(c[t]);
+                const double b = (double)Elem<T>::to_f32(p[t]);
+                n[0] += fabs(a - b);
+                d[0] += fabs(b);
+            }
+        }
+    } else {
+        const int64_t seg = (chunk_elems + bpc - 1) / bpc;
+        const int64_t lo = (int64_t)bi * seg;
+        const int64_t hi = (lo + seg < chunk_elems) ? lo + seg : chunk_elems;
+        for (int64_t i = lo + tid; i < hi; i += kThreads) {
+            const double a = (double)Elem<T>::to_f32(c[i]);
+            const double b = (double)Elem<T>::to_f32(p[i]);
+            n[0] += fabs(a - b);
+            d[0] += fabs(b);
+        }
+    }
+    double ns = (n[0] + n[1]) + (n[2] + n[3]);
+    double ds = (d[0] + d[1]) + (d[2] + d[3]);
+    ns = wave_sum(ns);
+    ds = wave_sum(ds);
+    __shared__ double sh[2][kThreads / FC_WAVE];
+    const int w = tid / FC_WAVE;
+    if ((tid & (FC_WAVE - 1)) == 0) { sh[0][w] = ns; sh[1][w] = ds; }
+    __syncthreads();
+    if (tid == 0) {
+        double a = 0.0, b = 0.0;
+#pragma unroll
+        for (int k = 0; k < kThreads / FC_WAVE; ++k) { a += sh[0][k]; b += sh[1][k]; }
+        partial[2 * (int64_t)blockIdx.x] = a;
+        partial[2 * (int64_t)blockIdx.x + 1] = b;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void decide_finalize_kernel(
+    const double* __restrict__ partial, int A, int bpc, const int32_t* __restrict__ step_idx,
+    int warmup_m, double eps, double* __restrict__ acc, double* __restrict__ l1rel,
+    uint8_t* __restrict__ mask, int32_t* __restrict__ idx, int32_t* __restrict__ n_rec) {
+    __shared__ double sh[2][kThreads];
+    __shared__ double tot[2][FC_MAX_ACTIVE];
+    const int tid = threadIdx.x;
+    for (int i = 0; i < A; ++i) {
+        double a = 0.0, b = 0.0;
+        for (int k = tid; k < bpc; k += kThreads) {
+            a += partial[2 * ((int64_t)i * bpc + k)];
+            b += partial[2 * ((int64_t)i * bpc + k) + 1];
+        }
+        sh[0][tid] = a;
+        sh[1][tid] = b;
+        __syncthreads();
+        for (int s = kThreads / 2; s > 0; s >>= 1) {
+            if (tid < s) { sh[0][tid] += sh[0][tid + s]; sh[1][tid] += sh[1][tid + s]; }
+            __syncthreads();
+        }
+        if (tid == 0) { tot[0][i] = sh[0][0]; tot[1][i] = sh[1][0]; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        int cnt = 0;
+        for (int i = 0; i < A; ++i) {
+            const double num = tot[0][i], den = tot[1][i];
+            const double rel = (den == 0.0) ? __longlong_as_double(0x7ff0000000000000LL) : num / den;
+            double f;
+            if (step_idx[i] < warmup_m) {
+                f = 0.0;                       // case 1: warm-up steps never reuse
+            } else {
+                const double a = acc[i] + rel;
+                f = (a > eps) ? 0.0 : a;       // case 2 / case 3
+            }
+            const bool rec = (f == 0.0);
+            acc[i] = f;
+            if (l1rel) l1rel[i] = rel;
+            mask[i] = rec ? 1 : 0;
+            if (rec) idx[cnt++] = i;
+        }
+        for (int i = cnt; i < A; ++i) idx[i] = -1;
+        *n_rec = cnt;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void gather_chunks_kernel(
+    const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t chunk_vecs,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ n_rec) {
+    const int r = blockIdx.y;
+    if (r >= *n_rec) return;
+    const int c = idx[r];
+    const uint4* s = src + (int64_t)c * chunk_vecs;
+    uint4* d = dst + (int64_t)r * chunk_vecs;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < chunk_vecs; i += stride)
+        d[i] = s[i];
+}
+
+// byte-granular variant for chunks whose size is not a multiple of 16 bytes
+__global__ __launch_bounds__(kThreads) void gather_chunks_bytes_kernel(
+    const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int64_t chunk_bytes,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ n_rec) {
+    const int r = blockIdx.y;
+    if (r >= *n_rec) return;
+    const int c = idx[r];
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < chunk_bytes; i += stride)
+        dst[(int64_t)r * chunk_bytes + i] = src[(int64_t)c * chunk_bytes + i];
+}
+
+template <typename T>
+int launch_typed(const FcDecideArgs& a, hipStream_t s) {
+    const int bpc = fc_decide_blocks_per_chunk(a.A, a.chunk_elems, a.dtype);
+    double* partial = reinterpret_cast<double*>(a.ws);
+    const int64_t chunk_bytes = a.chunk_elems * (int64_t)sizeof(T);
+    const bool vec = (chunk_bytes % 16 == 0) && ((uintptr_t)a.x_cur % 16 == 0) &&
+                     ((uintptr_t)a.x_prev % 16 == 0);
+    const dim3 grid(a.A * bpc);
+    if (vec)
+        decide_reduce_kernel<T, true><<<grid, kThreads, 0, s>>>(
+            (const T*)a.x_cur, (const T*)a.x_prev, a.chunk_elems, bpc, partial);
+    else
+        decide_reduce_kernel<T, false><<<grid, kThreads, 0, s>>>(
+            (const T*)a.x_cur, (const T*)a.x_prev, a.chunk_elems, bpc, partial);
+    FC_LAUNCH_CHECK();
+    decide_finalize_kernel<<<1, kThreads, 0, s>>>(partial, a.A, bpc, a.step_idx, a.warmup_m,
+                                                  a.eps, a.acc, a.l1rel, a.mask, a.idx, a.n_rec);
+    FC_LAUNCH_CHECK();
+    if (a.x_compact) {
+        const bool cvec = vec && ((uintptr_t)a.x_compact % 16 == 0);
+        if (cvec) {
+            const int64_t vecs = chunk_bytes / 16;
+            int gx = (int)((vecs + kThreads * 4 - 1) / (kThreads * 4));
+            gx = gx < 1 ? 1 : (gx > 1024 ? 1024 : gx);
+            gather_chunks_kernel<<<dim3(gx, a.A), kThreads, 0, s>>>(
+                (const uint4*)a.x_cur, (uint4*)a.x_compact, vecs, a.idx, a.n_rec);
+        } else {
+            int gx = (int)((chunk_bytes + kThreads * 16 - 1) / (kThreads * 16));
+            gx = gx < 1 ? 1 : (gx > 1024 ? 1024 : gx);
+            gather_chunks_bytes_kernel<<<dim3(gx, a.A), kThreads, 0, s>>>(
+                (const uint8_t*)a.x_cur, (uint8_t*)a.x_compact, chunk_bytes, a.idx, a.n_rec);
+        }
+        FC_LAUNCH_CHECK();
+    }
+    return FC_OK;
+}
+
+}  // namespace
+
+int fc_decide_blocks_per_chunk(int A, int64_t chunk_elems, fc_dtype dtype) {
+    // about 8 blocks per compute unit over the whole launch, at least 4 KB of each operand
+    // per block-iteration
+    const int vec = (dtype == FC_BF16) ? 8 : 4;
+    int64_t want = 2048 / A;
+    int64_t max_useful = (chunk_elems / vec + kThreads - 1) / kThreads;
+    if (max_useful < 1) max_useful = 1;
+    if (want > max_useful) want = max_useful;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+
+int fc_launch_decide(const FcDecideArgs& a, hipStream_t s) {
+    return a.dtype == FC_BF16 ? launch_typed<bf16_t>(a, s) : launch_typed<float>(a, s);
+}

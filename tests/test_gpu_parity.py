@@ -1,0 +1,332 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 oracle, element by element on
+the same seeded inputs.  Bars: decisions and kept indices bit-exact; attention within
+1e-5 relative (fp32) / 2e-2 max-abs (bf16, plus 1e-2 relative Frobenius)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flowcache_oracle as O
+from paper_2602_10825_amd import binding as B
+from paper_2602_10825_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def dev(arr, dtype):
+    return B.to_device(arr, dtype, DEV)
+
+
+# ------------------------------------------------------------------ decide + gather
+def run_decide(wl, d, eps=None, warmup_m=None, gather=True):
+    xc, xp = dev(d["x_cur"], wl.dtype), dev(d["x_prev"], wl.dtype)
+    acc = torch.from_numpy(d["acc"].copy()).to(DEV)
+    step = torch.from_numpy(d["step_idx"]).to(DEV)
+    eps = wl.eps if eps is None else eps
+    m = wl.warmup_m if warmup_m is None else warmup_m
+    out = B.flowcache_chunk_decide(xc, xp, step, m, eps, acc, gather=gather)
+    torch.cuda.synchronize()
+    ref = O.chunk_decide(d["x_cur"], d["x_prev"], d["step_idx"], m, eps, d["acc"])
+    return out, ref
+
+
+def check_decide(wl, d, out, ref):
+    assert ref["margin"].min() > 1e-9, "generator produced a knife-edge decision"
+    assert out["recompute_mask"].cpu().numpy().tolist() == ref["mask"].tolist()
+    n = int(out["n_recompute"].item())
+    assert n == int(ref["n_recompute"])
+    idx = out["recompute_idx"].cpu().numpy()
+    assert idx[:n].tolist() == ref["recompute_idx"].tolist() and np.all(idx[n:] == -1)
+    got_l1 = out["l1rel"].cpu().numpy()
+    assert np.allclose(got_l1, ref["l1rel"], rtol=1e-12, atol=0)
+    assert np.allclose(out["acc"].cpu().numpy(), ref["acc"], rtol=1e-12, atol=0)
+    if out["x_compact"] is not None and n:
+        xc = B.to_host(out["x_compact"])
+        assert np.array_equal(xc[:n], O.gather_chunks(d["x_cur"], ref["recompute_idx"]))
+
+
+@pytest.mark.parametrize("wl,sig", [(synth.C1, None), (synth.C1, [0.1, 0.001]),
+                                    (synth.MID_BF16, [0.003, 0.5, 0.02]),
+                                    (synth.MID_F32, [0.2, 0.001, 0.04])])
+def test_decide_matches_oracle(wl, sig):
+    d = synth.decide_inputs(wl, seed=0, sigmas=sig)
+    out, ref = run_decide(wl, d)
+    check_decide(wl, d, out, ref)
+    assert 0 < int(ref["n_recompute"]) < wl.A          # mixed reuse / recompute
+
+
+def test_decide_eps_zero_warmup_and_zero_denominator():
+    wl = synth.C1
+    d = synth.decide_inputs(wl, seed=1)
+    out, ref = run_decide(wl, d, eps=0.0)
+    assert out["recompute_mask"].cpu().tolist() == [1, 1] == ref["mask"].tolist()
+    d2 = synth.decide_inputs(wl, seed=1, sigmas=[1e-4, 1e-4], step_idx=[1, 9])
+    out, ref = run_decide(wl, d2)
+    check_decide(wl, d2, out, ref)
+    assert ref["mask"].tolist() == [1, 0]                 # warm-up chunk computes
+    d3 = synth.decide_inputs(wl, seed=1)
+    d3["x_prev"][0] = 0
+    out, ref = run_decide(wl, d3)
+    assert np.isinf(out["l1rel"].cpu().numpy()[0]) and out["recompute_mask"].cpu().tolist()[0] == 1
+    d3["x_cur"][0] = 0                                     # 0/0
+    out, ref = run_decide(wl, d3)
+    assert out["recompute_mask"].cpu().tolist()[0] == 1 == ref["mask"][0]
+
+
+@pytest.mark.parametrize("dtype,elems", [("bf16", 1003), ("f32", 4099), ("bf16", 8 * 3000 + 8),
+                                         ("f32", 7), ("bf16", 1)])
+def test_decide_ragged_and_unaligned_chunks(dtype, elems):
+    wl = synth.Workload("t", dtype, 1, 1, elems, 3, 1, 0, 1, warmup_m=2, eps=0.05)
+    d = synth.decide_inputs(wl, seed=2, sigmas=[0.001, 0.2, 0.01])
+    out, ref = run_decide(wl, d)
+    check_decide(wl, d, out, ref)
+
+
+def test_decide_accumulates_over_ticks_like_the_oracle():
+    wl = synth.Workload("t", "bf16", 2, 2, 64, 4, 96, 0, 1, warmup_m=2, eps=0.1)
+    rng = np.random.default_rng(0)
+    acc_ref = np.zeros(wl.A)
+    acc_gpu = torch.zeros(wl.A, dtype=torch.float64, device=DEV)
+    x_prev = synth.to_storage(rng.standard_normal((wl.A, wl.chunk_elems)).astype(np.float32), "bf16")
+    masks = []
+    for tick in range(12):
+        sig = np.array([0.03, 0.012, 0.06, 0.2])
+        x_cur = synth.to_storage((O.widen(x_prev) + sig[:, None] * rng.standard_normal(x_prev.shape)
+                                  ).astype(np.float32), "bf16")
+        step = np.array([tick, tick + 1, tick, max(0, tick - 3)], dtype=np.int32)
+        ref = O.chunk_decide(x_cur, x_prev, step, wl.warmup_m, wl.eps, acc_ref)
+        out = B.flowcache_chunk_decide(dev(x_cur, "bf16"), dev(x_prev, "bf16"),
+                                       torch.from_numpy(step).to(DEV), wl.warmup_m, wl.eps, acc_gpu)
+        assert out["recompute_mask"].cpu().numpy().tolist() == ref["mask"].tolist(), tick
+        assert np.allclose(acc_gpu.cpu().numpy(), ref["acc"], rtol=1e-12)
+        acc_ref = ref["acc"]
+        masks.append(ref["mask"].tolist())
+        x_prev = x_cur
+    assert any(0 in m for m in masks) and any(m.count(1) > 1 for m in masks)
+
+
+# ------------------------------------------------------------------ attention
+def run_attend(wl, a, rec, mass_len=0, obs_window=50, scale=0.0):
+    A = wl.A
+    q_all = a["q"].reshape(A, wl.L_c, wl.H_q, wl.d)
+    kn_all = a["k_new"].reshape(A, wl.L_c, wl.H_k, wl.d)
+    vn_all = a["v_new"].reshape(A, wl.L_c, wl.H_k, wl.d)
+    R = len(rec)
+    pad = [0] * (A - R)
+    order = list(rec) + pad
+    q_c = np.concatenate([q_all[c] for c in order]).reshape(A * wl.L_c, wl.H_q, wl.d)
+    kn_c = np.concatenate([kn_all[c] for c in order]).reshape(A * wl.L_c, wl.H_k, wl.d)
+    vn_c = np.concatenate([vn_all[c] for c in order]).reshape(A * wl.L_c, wl.H_k, wl.d)
+    idx = torch.tensor(list(rec) + [-1] * (A - R), dtype=torch.int32, device=DEV)
+    n = torch.tensor([R], dtype=torch.int32, device=DEV)
+    kc, vc = dev(a["k_cache"], wl.dtype), dev(a["v_cache"], wl.dtype)
+    qd = dev(q_c, wl.dtype)
+    out0 = torch.full_like(qd, 7.0)
+    res = B.flowcache_attend(qd, dev(kn_c, wl.dtype), dev(vn_c, wl.dtype), kc, vc, wl.L_c,
+                             wl.L_clean, a["active_off"], idx, n, softmax_scale=scale, out=out0,
+                             mass_len=mass_len, obs_window=obs_window)
+    torch.cuda.synchronize()
+    # oracle on the same bits
+    kc_ref = O.scatter_kv(a["k_cache"], kn_c[:R * wl.L_c], rec, a["active_off"], wl.L_c)
+    vc_ref = O.scatter_kv(a["v_cache"], vn_c[:R * wl.L_c], rec, a["active_off"], wl.L_c)
+    assert np.array_equal(B.to_host(kc), kc_ref) and np.array_equal(B.to_host(vc), vc_ref)
+    ref_out, ref_lse = O.attend(q_c[:R * wl.L_c], kc_ref, vc_ref, wl.L_clean, a["active_off"], wl.L_c,
+                                rec, scale=(scale if scale > 0 else None))
+    got = O.widen(B.to_host(res["out"]))
+    assert np.all(got[R * wl.L_c:] == 7.0)               # rows of non-recomputed blocks untouched
+    return got[:R * wl.L_c], ref_out, res, ref_lse, q_c, kc_ref
+
+
+def check_attend(wl, got, ref, res, ref_lse, R):
+    err = np.abs(got - ref)
+    if wl.dtype == "f32":
+        assert err.max() / np.abs(ref).max() <= 1e-5
+        row = np.sqrt((err ** 2).sum(-1)) / np.sqrt((ref ** 2).sum(-1))
+        assert row.max() <= 1e-5
+        lse_tol = 1e-5
+    else:
+        assert err.max() <= 2e-2
+        assert np.sqrt((err ** 2).sum()) / np.sqrt((ref ** 2).sum()) <= 1e-2
+        lse_tol = 2e-2
+    lse = res["lse"].cpu().numpy()[:, :R * wl.L_c]
+    assert np.abs(lse - ref_lse).max() <= lse_tol
+
+
+@pytest.mark.parametrize("wl,rec", [
+    (synth.C1, [0, 1]), (synth.C1, [1]), (synth.C1_MHA, [0, 1]), (synth.C1_MHA, [0]),
+    (synth.MID_F32, [0, 1, 2]), (synth.MID_F32, [0, 2]), (synth.MID_F32_D128, [1, 2]),
+    (synth.MID_BF16, [0, 1, 2]), (synth.MID_BF16, [2]), (synth.MID_BF16, [0, 2]),
+    (synth.MID_BF16_GQA, [0, 1, 2]), (synth.MID_BF16_GQA, [1]),
+])
+def test_attend_matches_oracle(wl, rec):
+    a = synth.attend_inputs(wl, seed=0)
+    got, ref, res, ref_lse, _, _ = run_attend(wl, a, rec)
+    check_attend(wl, got, ref, res, ref_lse, len(rec))
+
+
+def test_attend_bf16_d64_and_noncontiguous_slots_and_scale():
+    wl = synth.Workload("t", "bf16", 4, 2, 64, 3, 150, 333, 100)
+    a = synth.attend_inputs(wl, seed=3)
+    got, ref, res, ref_lse, _, _ = run_attend(wl, a, [0, 1, 2], scale=0.2)
+    check_attend(wl, got, ref, res, ref_lse, 3)
+    # slots in a different physical order with gaps: capacity grows, offsets permuted
+    wl2 = synth.Workload("t2", "bf16", 2, 2, 128, 3, 70, 100, 50)
+    a2 = synth.attend_inputs(wl2, seed=4)
+    cap = wl2.capacity + 200
+    kc = np.zeros((wl2.H_k, cap, wl2.d), np.uint16); vc = np.zeros_like(kc)
+    kc[:, :wl2.capacity] = a2["k_cache"]; vc[:, :wl2.capacity] = a2["v_cache"]
+    a2["k_cache"], a2["v_cache"] = kc, vc
+    a2["active_off"] = np.array([wl2.L_clean + 160, wl2.L_clean + 8, wl2.L_clean + 240], np.int32)
+    got, ref, res, ref_lse, _, _ = run_attend(wl2, a2, [0, 1, 2])
+    check_attend(wl2, got, ref, res, ref_lse, 3)
+
+
+def test_attend_no_clean_context_and_nothing_to_recompute():
+    wl = synth.Workload("t", "f32", 2, 2, 64, 2, 90, 0, 1)
+    a = synth.attend_inputs(wl, seed=5)
+    got, ref, res, ref_lse, _, _ = run_attend(wl, a, [0, 1])
+    check_attend(wl, got, ref, res, ref_lse, 2)
+    wlb = synth.Workload("t", "bf16", 2, 2, 128, 2, 90, 0, 1)
+    ab = synth.attend_inputs(wlb, seed=5)
+    got, ref, res, ref_lse, _, _ = run_attend(wlb, ab, [0, 1])
+    check_attend(wlb, got, ref, res, ref_lse, 2)
+    got, ref, res, _, _, _ = run_attend(wlb, ab, [])      # R = 0: no row written, cache untouched
+    assert got.shape[0] == 0
+
+
+# ------------------------------------------------------------------ importance mass
+@pytest.mark.parametrize("wl,W", [(synth.C1, 50), (synth.C1_MHA, 50), (synth.MID_BF16, 50),
+                                  (synth.MID_BF16_GQA, 0), (synth.MID_F32, 100)])
+def test_mass_matches_oracle(wl, W):
+    a = synth.attend_inputs(wl, seed=0)
+    rec = list(range(wl.A))
+    mass_len = wl.L_clean + wl.L_c                        # clean region + the finished chunk
+    got, ref, res, _, q_c, kc_ref = run_attend(wl, a, rec, mass_len=mass_len, obs_window=W)
+    q_obs = O.observation_rows(q_c, len(rec), wl.L_c, W)
+    ref_mass = O.attention_mass(q_obs, kc_ref, mass_len)
+    mass = res["mass"].cpu().numpy().astype(np.float64)
+    assert np.all(mass >= 0) and np.allclose(mass.sum(axis=1), 1.0, atol=1e-4)
+    rel_l1 = np.abs(mass - ref_mass).sum(axis=1) / ref_mass.sum(axis=1)
+    assert rel_l1.max() <= (1e-5 if wl.dtype == "f32" else 1e-2)
+    # the standalone entry point gives the same bits for the same rows
+    m2 = B.flowcache_attention_mass(dev(np.ascontiguousarray(q_obs), wl.dtype),
+                                    dev(kc_ref, wl.dtype), mass_len)
+    assert torch.equal(m2, res["mass"])
+
+
+def test_mass_is_nan_when_last_chunk_is_not_recomputed():
+    wl = synth.C1
+    a = synth.attend_inputs(wl, seed=0)
+    _, _, res, _, _, _ = run_attend(wl, a, [0], mass_len=wl.L_clean)
+    assert torch.isnan(res["mass"]).all()
+
+
+# ------------------------------------------------------------------ compression
+def run_compress(wl, c, L_k, budget, pool_k=7, lam=0.07):
+    k, v = dev(c["k"], wl.dtype), dev(c["v"], wl.dtype)
+    mass = torch.from_numpy(c["mass"][:, :L_k].copy()).to(DEV)
+    kept = B.flowcache_kv_compress(k, v, L_k, budget, mass, pool_k, lam)
+    torch.cuda.synchronize()
+    rk, rk_k, rk_v, sc = O.kv_compress(c["k"], c["v"], L_k, budget, c["mass"][:, :L_k], pool_k, lam)
+    gaps = [O.boundary_gap(sc[h], budget) for h in range(wl.H_k)]
+    assert all(g == 0.0 or g > 1e-12 for g in gaps), f"ambiguous boundary {gaps}"
+    assert np.array_equal(kept.cpu().numpy(), rk)
+    assert np.array_equal(B.to_host(k), rk_k) and np.array_equal(B.to_host(v), rk_v)
+    return kept, rk
+
+
+@pytest.mark.parametrize("wl,kind", [(synth.C1, "normal"), (synth.C1_MHA, "clustered"),
+                                     (synth.MID_BF16, "normal"), (synth.MID_BF16, "clustered"),
+                                     (synth.MID_BF16, "heavy_dup"), (synth.MID_F32, "heavy_dup"),
+                                     (synth.MID_F32_D128, "clustered"), (synth.MID_BF16_GQA, "normal")])
+def test_compress_matches_oracle(wl, kind):
+    c = synth.compress_inputs(wl, seed=0, kind=kind)
+    run_compress(wl, c, wl.L_k, wl.budget)
+
+
+@pytest.mark.parametrize("pool_k,lam,budget", [(1, 1.0, 100), (7, 0.0, 100), (15, 0.5, 1),
+                                               (3, 0.07, 999), (7, 0.07, 1000), (7, 0.07, 5000)])
+def test_compress_parameter_corners(pool_k, lam, budget):
+    wl = synth.MID_BF16
+    c = synth.compress_inputs(wl, seed=1, kind="clustered")
+    kept, rk = run_compress(wl, c, wl.L_k, budget, pool_k, lam)
+    if budget >= wl.L_k:
+        assert kept.shape[1] == wl.L_k and np.array_equal(rk[0], np.arange(wl.L_k))
+
+
+def test_compress_exact_ties_and_bf16_d64():
+    # duplicated keys + mass plateaus give exactly equal scores: lower position must win
+    wl = synth.Workload("t", "bf16", 2, 2, 64, 1, 8, 600, 300)
+    c = synth.compress_inputs(wl, seed=2)
+    c["k"][:, 300:600] = c["k"][:, 0:300]
+    c["mass"][:] = np.float32(1.0 / 600)
+    kept, rk = run_compress(wl, c, 600, 300)
+    sc = O.selection_scores(c["k"][0], c["mass"][0], 7, 0.07)
+    assert np.array_equal(sc[:300], sc[300:])             # the ties are real
+    wl2 = synth.Workload("t", "f32", 1, 1, 64, 1, 8, 64, 32)
+    c2 = synth.compress_inputs(wl2, seed=3)
+    c2["k"][:] = c2["k"][:, :1]
+    c2["mass"][:] = np.float32(0.5)
+    kept, rk = run_compress(wl2, c2, 64, 32)
+    assert kept.cpu().numpy()[0].tolist() == list(range(32))
+
+
+def test_compress_on_strided_cache_prefix_leaves_the_rest_untouched():
+    wl = synth.MID_BF16
+    c = synth.compress_inputs(wl, seed=4)
+    cap = wl.L_k + 77
+    kfull = np.random.default_rng(0).integers(0, 2 ** 15, (wl.H_k, cap, wl.d)).astype(np.uint16)
+    vfull = kfull[::-1].copy()
+    kfull[:, :wl.L_k] = c["k"]; vfull[:, :wl.L_k] = c["v"]
+    run_compress(wl, {"k": kfull, "v": vfull, "mass": c["mass"]}, wl.L_k, wl.budget)
+
+
+# ------------------------------------------------------------------ the whole step, chained
+@pytest.mark.parametrize("wl,eps", [(synth.C1, None), (synth.C1, 0.0), (synth.MID_BF16, 0.0)])
+def test_full_step_chain(wl, eps):
+    d = synth.decide_inputs(wl, seed=0)
+    a = synth.attend_inputs(wl, seed=0)
+    eps = wl.eps if eps is None else eps
+    # force the last chunk into warm-up so it is recomputed and can serve as observation rows
+    d["step_idx"][-1] = 0
+    xc, xp = dev(d["x_cur"], wl.dtype), dev(d["x_prev"], wl.dtype)
+    acc = torch.zeros(wl.A, dtype=torch.float64, device=DEV)
+    dec = B.flowcache_chunk_decide(xc, xp, torch.from_numpy(d["step_idx"]).to(DEV), wl.warmup_m, eps,
+                                   acc, gather=False)
+    ref = O.chunk_decide(d["x_cur"], d["x_prev"], d["step_idx"], wl.warmup_m, eps, d["acc"])
+    rec = ref["recompute_idx"].tolist()
+    assert dec["recompute_mask"].cpu().tolist() == ref["mask"].tolist()
+    if eps == 0.0:
+        assert rec == list(range(wl.A))
+    A, R = wl.A, len(rec)
+    order = rec + [0] * (A - R)
+    pick = lambda arr, H: np.concatenate([arr.reshape(A, wl.L_c, H, wl.d)[c] for c in order])
+    q_c, kn_c, vn_c = pick(a["q"], wl.H_q), pick(a["k_new"], wl.H_k), pick(a["v_new"], wl.H_k)
+    kc, vc = dev(a["k_cache"], wl.dtype), dev(a["v_cache"], wl.dtype)
+    mass_len = wl.L_clean + wl.L_c
+    res = B.flowcache_attend(dev(q_c, wl.dtype), dev(kn_c, wl.dtype), dev(vn_c, wl.dtype), kc, vc,
+                             wl.L_c, wl.L_clean, a["active_off"], dec["recompute_idx"],
+                             dec["n_recompute"], mass_len=mass_len, obs_window=wl.obs_window)
+    kc_ref = O.scatter_kv(a["k_cache"], kn_c[:R * wl.L_c], rec, a["active_off"], wl.L_c)
+    vc_ref = O.scatter_kv(a["v_cache"], vn_c[:R * wl.L_c], rec, a["active_off"], wl.L_c)
+    ref_out, _ = O.attend(q_c[:R * wl.L_c], kc_ref, vc_ref, wl.L_clean, a["active_off"], wl.L_c, rec)
+    got = O.widen(B.to_host(res["out"]))[:R * wl.L_c]
+    tol = 1e-5 * np.abs(ref_out).max() if wl.dtype == "f32" else 2e-2
+    assert np.abs(got - ref_out).max() <= tol
+    if eps == 0.0:   # equals uncached full chunk-causal attention built directly from k_new
+        kfull = np.concatenate([a["k_cache"][:, :wl.L_clean], np.transpose(a["k_new"], (1, 0, 2))], 1)
+        vfull = np.concatenate([a["v_cache"][:, :wl.L_clean], np.transpose(a["v_new"], (1, 0, 2))], 1)
+        unc, _ = O.attend(a["q"], kfull, vfull, wl.L_clean, a["active_off"], wl.L_c, list(range(A)))
+        assert np.abs(got - unc).max() <= tol
+    # commit: compress [clean | chunk 0] with the mass the GPU emitted (shared-mass protocol)
+    mass_gpu = res["mass"]
+    ref_mass = O.attention_mass(O.observation_rows(q_c, R, wl.L_c, wl.obs_window), kc_ref, mass_len)
+    m = mass_gpu.cpu().numpy().astype(np.float64)
+    assert (np.abs(m - ref_mass).sum(1) / ref_mass.sum(1)).max() <= (1e-5 if wl.dtype == "f32" else 1e-2)
+    budget = wl.budget
+    kept = B.flowcache_kv_compress(kc, vc, mass_len, budget, mass_gpu, wl.pool_k, wl.lam)
+    torch.cuda.synchronize()
+    rk, rk_k, rk_v, _ = O.kv_compress(kc_ref, vc_ref, mass_len, budget, mass_gpu.cpu().numpy(),
+                                      wl.pool_k, wl.lam)
+    assert np.array_equal(kept.cpu().numpy(), rk)
+    assert np.array_equal(B.to_host(kc), rk_k) and np.array_equal(B.to_host(vc), rk_v)
