@@ -11,6 +11,8 @@
  *   flowcache_attend          chunk-causal multi-head attention of the recompute chunks
  *                             against [clean KV cache | active chunks' KV], optionally
  *                             emitting the per-key attention mass (Sec. 3.3, Eq. (9)).
+ *   flowcache_scatter_kv      new K/V of the recompute chunks into their cache slots (the
+ *                             scatter half of the gather step; Sec. 3.2).
  *   flowcache_attention_mass  the importance mass alone, for explicit observation queries
  *                             (Sec. 3.3, Eq. (9); observation window of App. C.2).
  *   flowcache_kv_compress     joint importance-redundancy scoring, per-head top-B selection
@@ -139,6 +141,19 @@ int flowcache_attend(const void* q, const void* k_new, const void* v_new, void* 
                      fc_stream stream);
 size_t flowcache_attend_workspace(int A, int L_c, int H_q, int H_k, int d, int mass_len,
                                   int obs_window);
+
+/*
+ * The K/V half of the gather/scatter step on its own (flowcache_attend performs it when
+ * k_new/v_new are given): block r < *n_recompute of the compact token-major k_new/v_new
+ * ([A*L_c, H_k, d]) is copied into slot active_off[recompute_idx[r]] of the head-major
+ * caches.  Sec. 3.2 (only the chunks chosen for recomputation produce new K/V); slots of
+ * reused chunks are not touched.  Arguments as in flowcache_attend.
+ */
+int flowcache_scatter_kv(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                         int64_t kv_head_stride, int64_t kv_tok_stride, int capacity,
+                         fc_dtype dtype, int H_k, int d, int L_c, int L_clean, int A,
+                         const int32_t* active_off, const int32_t* recompute_idx,
+                         const int32_t* n_recompute, fc_stream stream);
 
 /*
  * Importance mass, Eq. (9), for explicit observation queries (App. C.2 uses the last 50

@@ -24,7 +24,7 @@ FC_MAX_ACTIVE = 16
 EXPORTS = (
     "flowcache_status_string", "flowcache_version",
     "flowcache_chunk_decide", "flowcache_chunk_decide_workspace",
-    "flowcache_attend", "flowcache_attend_workspace",
+    "flowcache_attend", "flowcache_attend_workspace", "flowcache_scatter_kv",
     "flowcache_attention_mass", "flowcache_attention_mass_workspace",
     "flowcache_kv_compress", "flowcache_kv_compress_workspace",
 )
@@ -65,6 +65,9 @@ def lib() -> ctypes.CDLL:
     L.flowcache_attend.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_int, c_int, c_int,
                                    c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_f, c_vp,
                                    c_vp, c_vp, c_int, c_int, c_vp, c_sz, c_vp]
+    L.flowcache_scatter_kv.restype = c_int
+    L.flowcache_scatter_kv.argtypes = [c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_int, c_int, c_int,
+                                       c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
     L.flowcache_attention_mass_workspace.restype = c_sz
     L.flowcache_attention_mass_workspace.argtypes = [c_int] * 5
     L.flowcache_attention_mass.restype = c_int
@@ -170,6 +173,23 @@ def flowcache_attend(q: torch.Tensor, k_new: Optional[torch.Tensor], v_new: Opti
                             workspace.numel(), _stream(stream))
     _check("flowcache_attend", st)
     return {"out": out, "lse": lse, "mass": mass}
+
+
+def flowcache_scatter_kv(k_new: torch.Tensor, v_new: torch.Tensor, k_cache: torch.Tensor,
+                         v_cache: torch.Tensor, L_c: int, L_clean: int, active_off: Sequence[int],
+                         recompute_idx: torch.Tensor, n_recompute: torch.Tensor, stream=None) -> None:
+    """Copy the recompute chunks' rows of k_new/v_new ``[A*L_c, H_k, d]`` into their slots."""
+    H_k, capacity, d = k_cache.shape
+    A = len(active_off)
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_cache.stride(2) == 1
+    assert v_cache.stride() == k_cache.stride()
+    off = (ctypes.c_int32 * A)(*[int(x) for x in active_off])
+    st = lib().flowcache_scatter_kv(_ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                    k_cache.stride(0), k_cache.stride(1), capacity,
+                                    _dtype_code(k_cache), H_k, d, int(L_c), int(L_clean), A,
+                                    ctypes.cast(off, ctypes.c_void_p), _ptr(recompute_idx),
+                                    _ptr(n_recompute), _stream(stream))
+    _check("flowcache_scatter_kv", st)
 
 
 def flowcache_attention_mass(q_obs: torch.Tensor, k_cache: torch.Tensor, mass_len: int,

@@ -97,6 +97,43 @@ int flowcache_attention_mass(const void* q_obs, int W, const void* k_cache,
     return fc_launch_mass(m, (hipStream_t)stream);
 }
 
+// ------------------------------------------------------------------ scatter_kv
+namespace {
+int check_slots(int A, int L_c, int L_clean, int capacity, const int32_t* active_off) {
+    // slots: inside [L_clean, capacity], L_c long, pairwise disjoint
+    for (int i = 0; i < A; ++i) {
+        const int64_t lo = active_off[i];
+        if (lo < L_clean || lo + L_c > capacity) return FC_INVALID_ARGUMENT;
+        for (int j = 0; j < i; ++j) {
+            const int64_t lj = active_off[j];
+            if (lo < lj + L_c && lj < lo + L_c) return FC_INVALID_ARGUMENT;
+        }
+    }
+    return FC_OK;
+}
+}  // namespace
+
+int flowcache_scatter_kv(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                         int64_t kv_head_stride, int64_t kv_tok_stride, int capacity,
+                         fc_dtype dtype, int H_k, int d, int L_c, int L_clean, int A,
+                         const int32_t* active_off, const int32_t* recompute_idx,
+                         const int32_t* n_recompute, fc_stream stream) {
+    if (!k_new || !v_new || !active_off || !recompute_idx || !n_recompute) return FC_INVALID_ARGUMENT;
+    if (A < 1 || A > FC_MAX_ACTIVE || L_c < 1 || L_clean < 0 || capacity < 1) return FC_INVALID_ARGUMENT;
+    int st = check_kv_layout(k_cache, v_cache, kv_head_stride, kv_tok_stride, capacity, dtype, H_k, d);
+    if (st != FC_OK) return st;
+    st = check_slots(A, L_c, L_clean, capacity, active_off);
+    if (st != FC_OK) return st;
+    if (!aligned16(k_new) || !aligned16(v_new)) return FC_UNSUPPORTED;
+    FcScatterArgs sc{};
+    sc.k_new = k_new; sc.v_new = v_new; sc.k_cache = k_cache; sc.v_cache = v_cache;
+    sc.head_stride = kv_head_stride; sc.tok_stride = kv_tok_stride; sc.dtype = dtype;
+    sc.H_k = H_k; sc.d = d; sc.L_c = L_c; sc.A = A;
+    std::memcpy(sc.active_off, active_off, sizeof(int32_t) * A);
+    sc.rec_idx = recompute_idx; sc.n_rec = n_recompute;
+    return fc_launch_scatter_kv(sc, (hipStream_t)stream);
+}
+
 // ------------------------------------------------------------------ attend
 size_t flowcache_attend_workspace(int A, int L_c, int H_q, int H_k, int d, int mass_len,
                                   int obs_window) {
@@ -127,15 +164,8 @@ int flowcache_attend(const void* q, const void* k_new, const void* v_new, void* 
     if (H_q % H_k != 0) return FC_INVALID_ARGUMENT;
     if (!(softmax_scale >= 0.f) || !std::isfinite(softmax_scale)) return FC_INVALID_ARGUMENT;
     if ((int64_t)A * L_c > INT32_MAX) return FC_UNSUPPORTED;
-    // slots: inside [L_clean, capacity], L_c long, pairwise disjoint
-    for (int i = 0; i < A; ++i) {
-        const int64_t lo = active_off[i];
-        if (lo < L_clean || lo + L_c > capacity) return FC_INVALID_ARGUMENT;
-        for (int j = 0; j < i; ++j) {
-            const int64_t lj = active_off[j];
-            if (lo < lj + L_c && lj < lo + L_c) return FC_INVALID_ARGUMENT;
-        }
-    }
+    st = check_slots(A, L_c, L_clean, capacity, active_off);
+    if (st != FC_OK) return st;
     if (!aligned16(q) || !aligned16(out) || (k_new && (!aligned16(k_new) || !aligned16(v_new))))
         return FC_UNSUPPORTED;
     if (mass) {
@@ -149,13 +179,9 @@ int flowcache_attend(const void* q, const void* k_new, const void* v_new, void* 
     hipStream_t s = (hipStream_t)stream;
 
     if (k_new) {
-        FcScatterArgs sc{};
-        sc.k_new = k_new; sc.v_new = v_new; sc.k_cache = k_cache; sc.v_cache = v_cache;
-        sc.head_stride = kv_head_stride; sc.tok_stride = kv_tok_stride; sc.dtype = dtype;
-        sc.H_k = H_k; sc.d = d; sc.L_c = L_c; sc.A = A;
-        std::memcpy(sc.active_off, active_off, sizeof(int32_t) * A);
-        sc.rec_idx = recompute_idx; sc.n_rec = n_recompute;
-        st = fc_launch_scatter_kv(sc, s);
+        st = flowcache_scatter_kv(k_new, v_new, k_cache, v_cache, kv_head_stride, kv_tok_stride,
+                                  capacity, dtype, H_k, d, L_c, L_clean, A, active_off,
+                                  recompute_idx, n_recompute, stream);
         if (st != FC_OK) return st;
     }
 
