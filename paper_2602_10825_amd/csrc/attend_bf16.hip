@@ -12,8 +12,13 @@
 //                 the accumulator layout already is the B-operand layout of the next
 //                 product (contraction index = key, with a fixed permutation of the keys
 //                 inside each 16-key group that V's LDS layout mirrors).
-//   O^T += V^T P^T  A = V^T fragment from LDS (V is stored transposed, keys permuted).
-// K/V tiles are fetched with 16-byte global loads one tile ahead of the compute.
+//   O^T += V^T P^T  A = V^T fragment read from the row-major V tile with the transposing
+//                 LDS load ds_read_b64_tr_b16 (each 16-lane group turns 4 keys x 16 dv into
+//                 16 lanes x 4 keys), two loads per 8-key fragment.
+// The running max is only raised (and O rescaled) when some row's max grew by more than
+// 2^8, so the rescale is rare; until then P is bounded by 256, harmless in fp32 / bf16.
+// K/V tiles are fetched with 16-byte global loads one tile ahead of the compute and
+// double-buffered in LDS: one barrier per tile.
 // Work-groups are mapped so that the 32 compute units of one XCD work on the same head
 // and chunk at the same time and share the K/V stream through that XCD's L2.
 #include "fc_common.hpp"
@@ -31,12 +36,15 @@ constexpr int NT = 256;      // threads
 constexpr int NXCD = 8;
 constexpr float kNegBig = -1.0e30f;
 
-// position of key `kk` (0..63) inside a row of the transposed V tile: the 8 keys that one
-// lane half contributes to one 16-key contraction step sit contiguously.
-__device__ __forceinline__ int vt_pos(int kk) {
-    const int kb = kk >> 5, w = kk & 31;
-    const int blk8 = w >> 3, hh = (w >> 2) & 1, ilo = w & 3;
-    return kb * 32 + (blk8 >> 1) * 16 + hh * 8 + (blk8 & 1) * 4 + ilo;
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
+// Transposing LDS load: within each group of 16 lanes, lane s passes the address of 4
+// consecutive bf16; lane i receives element (i % 4) of the data addressed by lanes
+// i/4, i/4 + 4, i/4 + 8, i/4 + 12.
+__device__ __forceinline__ s16x4_t lds_read_tr(const bf16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4_t __attribute__((address_space(3)))*)(p));
 }
 
 struct TileIter {
@@ -44,14 +52,45 @@ struct TileIter {
     bool done;
 };
 
+template <int LD, int ROWS_PER_PASS>
+__device__ __forceinline__ void prefetch_tile(uint4 (&kreg)[LD], uint4 (&vreg)[LD],
+                                              const bf16_t* kbase, const bf16_t* vbase,
+                                              const TileIter& t, int64_t tok_stride, int ld_row,
+                                              int ld_col) {
+    const int nvalid = (t.len - t.t0 < BK) ? t.len - t.t0 : BK;
+#pragma unroll
+    for (int p = 0; p < LD; ++p) {
+        int row = p * ROWS_PER_PASS + ld_row;
+        if (row > nvalid - 1) row = nvalid - 1;
+        const int64_t off = (int64_t)(t.start + t.t0 + row) * tok_stride + ld_col * 8;
+        kreg[p] = *reinterpret_cast<const uint4*>(kbase + off);
+        vreg[p] = *reinterpret_cast<const uint4*>(vbase + off);
+    }
+}
+
+template <int LD, int ROWS_PER_PASS>
+__device__ __forceinline__ void stage_tile(const uint4 (&kreg)[LD], const uint4 (&vreg)[LD],
+                                           bf16_t* Kb, bf16_t* Vb, int krow, int vrow, int ld_row,
+                                           int ld_col) {
+#pragma unroll
+    for (int p = 0; p < LD; ++p) {
+        const int row = p * ROWS_PER_PASS + ld_row;
+        *reinterpret_cast<uint4*>(&Kb[row * krow + ld_col * 8]) = kreg[p];
+        *reinterpret_cast<uint4*>(&Vb[row * vrow + ld_col * 8]) = vreg[p];
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int tiles, int per) {
     constexpr int KS = D / 16;        // contraction steps of Q K^T
     constexpr int DVB = D / 32;       // 32-wide blocks of the value dimension
-    constexpr int KROW = D + 8;       // padded K row (bf16 elements)
-    constexpr int VROW = BK + 8;      // padded V^T row
+    constexpr int KROW = D + 8;       // padded K row (bf16): 16-byte fragment reads of 16
+                                      // consecutive keys fall in distinct banks
+    constexpr int VROW = D + 32;      // padded V row: the 4 key rows of one transposing
+                                      // load fall in disjoint bank quarters
     constexpr int VPR = D / 8;        // 16-byte vectors per K/V row
     constexpr int LD = BK * VPR / NT; // global loads per thread per tile (K, and again V)
+    constexpr float kRaise = 8.0f;    // raise the running max only past this many octaves
 
     const int bid = blockIdx.x;
     const int xcd = bid % NXCD, slot = bid / NXCD;
@@ -69,8 +108,8 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, hh = lane >> 5;
 
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[BK * KROW];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[D * VROW];
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[2][BK * KROW];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][BK * VROW];
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[q = l32][16*step + 8*hh ..+8)
     bf16x8_t qf[2][KS];
@@ -111,65 +150,56 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
             if (len > 0) { t.start = start; t.len = len; t.t0 = 0; return; }
         }
         t.done = true;
+        t.t0 = 0;   // start/len still describe the last segment: a valid address range
     };
     it.sgi = -1; it.start = 0; it.len = 0; it.t0 = 0; it.done = false;
     next_segment(it);
 
+    // Global -> register prefetch of one tile (rows past the end of a segment are clamped
+    // to its last row) and its later store to LDS.
     uint4 kreg[LD], vreg[LD];
-    auto prefetch = [&](const TileIter& t) {
-        const int nvalid = (t.len - t.t0 < BK) ? t.len - t.t0 : BK;
-#pragma unroll
-        for (int p = 0; p < LD; ++p) {
-            const int idx = p * NT + tid;
-            int row = idx / VPR;
-            const int col = idx % VPR;
-            if (row > nvalid - 1) row = nvalid - 1;
-            const int64_t off = (int64_t)(t.start + t.t0 + row) * a.tok_stride + col * 8;
-            kreg[p] = *reinterpret_cast<const uint4*>(kbase + off);
-            vreg[p] = *reinterpret_cast<const uint4*>(vbase + off);
-        }
-    };
-    if (!it.done) prefetch(it);
+    const int ld_row = tid / VPR, ld_col = tid % VPR;
+    // per-lane offsets of the fragment reads
+    const int k_frag_off = l32 * KROW + 8 * hh;
+    // transposing V read: lane s of a 16-lane group addresses key (s/4), dv 4*(s%4) of the
+    // group's 4-key x 16-dv patch; groups 0/1 cover dv 0-15 / 16-31, lane half = key half
+    const int l16 = lane & 15;
+    const int v_frag_off = (hh * 4 + (l16 >> 2)) * VROW + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
+
+    prefetch_tile<LD, NT / VPR>(kreg, vreg, kbase, vbase, it, a.tok_stride, ld_row, ld_col);
+    stage_tile<LD, NT / VPR>(kreg, vreg, Ks[0], Vs[0], KROW, VROW, ld_row, ld_col);
+    __syncthreads();
+    int buf = 0;
 
     while (!it.done) {
         const int nvalid = (it.len - it.t0 < BK) ? it.len - it.t0 : BK;
-        // advance the iterator (scalar work) before the barrier
         it.t0 += BK;
         if (it.t0 >= it.len) next_segment(it);
+        // next tile: in flight during the compute (unconditional: after the last tile the
+        // iterator points at a valid tile again and the loaded data is simply not used)
+        prefetch_tile<LD, NT / VPR>(kreg, vreg, kbase, vbase, it, a.tok_stride, ld_row, ld_col);
 
-        __syncthreads();  // every wave is done reading the previous tile
-#pragma unroll
-        for (int p = 0; p < LD; ++p) {
-            const int idx = p * NT + tid;
-            const int row = idx / VPR, col = idx % VPR;
-            *reinterpret_cast<uint4*>(&Ks[row * KROW + col * 8]) = kreg[p];
-            const int pos = vt_pos(row);
-            const uint32_t w[4] = {vreg[p].x, vreg[p].y, vreg[p].z, vreg[p].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                Vt[(col * 8 + 2 * e) * VROW + pos] = (bf16_t)(w[e] & 0xffffu);
-                Vt[(col * 8 + 2 * e + 1) * VROW + pos] = (bf16_t)(w[e] >> 16);
-            }
-        }
-        __syncthreads();
-        if (!it.done) prefetch(it);
+        const bf16_t* Kb = Ks[buf];
+        const bf16_t* Vb = Vs[buf];
 
-        // ---- S^T = K Q^T : acc[qb][kb], lane: query l32, keys kb*32 + (r/4)*8 + hh*4 + r%4
+        // ---- S^T = K Q^T : sacc[qb][kb], lane: query l32, keys kb*32 + (i/4)*8 + hh*4 + i%4
         f32x16_t sacc[2][2];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[qb][kb][i] = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int st = 0; st < KS; ++st) {
                 const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(
-                    &Ks[(kb * 32 + l32) * KROW + 16 * st + 8 * hh]);
-                sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], sacc[0][kb], 0, 0, 0);
-                sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], sacc[1][kb], 0, 0, 0);
+                    &Kb[kb * 32 * KROW + k_frag_off + 16 * st]);
+                if (st == 0) {
+                    f32x16_t z;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) z[i] = 0.f;
+                    sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], z, 0, 0, 0);
+                    sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], z, 0, 0, 0);
+                } else {
+                    sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], sacc[0][kb], 0, 0, 0);
+                    sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], sacc[1][kb], 0, 0, 0);
+                }
             }
         }
         if (nvalid < BK) {  // ragged tail of a segment: mask the keys past its end
@@ -182,46 +212,69 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
                 }
         }
 
-        // ---- online softmax, P^T packed to bf16 (B operand of the next product)
+        // ---- running max: raised (with a rescale of O and l) only when some row grew a lot
+        float mx[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            float v = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);
+#pragma unroll
+            for (int i = 1; i < 16; ++i) v = fmaxf(v, fmaxf(sacc[qb][0][i], sacc[qb][1][i]));
+            v = fmaxf(v, __shfl_xor(v, 32, FC_WAVE));
+            mx[qb] = v * c2;
+        }
+        if (__any((mx[0] > m[0] + kRaise) || (mx[1] > m[1] + kRaise))) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const float mnew = fmaxf(m[qb], mx[qb]);
+                const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
+                m[qb] = mnew;
+                lsum[qb] *= alpha;
+#pragma unroll
+                for (int dv = 0; dv < DVB; ++dv)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[qb][dv][i] *= alpha;
+            }
+        }
+
+        // ---- P^T = exp2(S^T c2 - m), packed to bf16 (B operand of the next product)
         bf16x8_t pf[2][4];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            float mx = sacc[qb][0][0];
+            const float mneg = -m[qb];
+            float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[qb][kb][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, FC_WAVE));
-            const float mnew = fmaxf(m[qb], mx * c2);
-            const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
-            m[qb] = mnew;
-            float ps = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i], c2, -mnew));
-                    ps += p;
-                    pf[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)p;
+                for (int i = 0; i < 16; i += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i], c2, mneg));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 1], c2, mneg));
+                    ps0 += p0;
+                    ps1 += p1;
+                    pf[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)p0;
+                    pf[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)p1;
                 }
-            lsum[qb] = lsum[qb] * alpha + ps;
-#pragma unroll
-            for (int dv = 0; dv < DVB; ++dv)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[qb][dv][i] *= alpha;
+            lsum[qb] += ps0 + ps1;
         }
 
-        // ---- O^T += V^T P^T
+        // ---- O^T += V^T P^T : 16-key steps t (keys t*16 ..), value blocks dv
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
 #pragma unroll
             for (int dv = 0; dv < DVB; ++dv) {
-                const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(
-                    &Vt[(dv * 32 + l32) * VROW + t * 16 + hh * 8]);
+                const bf16_t* vp = &Vb[t * 16 * VROW + v_frag_off + dv * 32];
+                const s16x4_t lo = lds_read_tr(vp);
+                const s16x4_t hi = lds_read_tr(vp + 8 * VROW);
+                const s16x8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
                 o[0][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[0][t], o[0][dv], 0, 0, 0);
                 o[1][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1][t], o[1][dv], 0, 0, 0);
             }
         }
+
+        if (!it.done)                     // the prefetched tile goes to the other buffer
+            stage_tile<LD, NT / VPR>(kreg, vreg, Ks[buf ^ 1], Vs[buf ^ 1], KROW, VROW, ld_row, ld_col);
+        __syncthreads();
+        buf ^= 1;
     }
 
     // ---- epilogue: normalise, store O (bf16) and the row log-sum-exp
