@@ -53,7 +53,7 @@ struct TileIter {
 };
 
 template <int LD, int ROWS_PER_PASS>
-__device__ __forceinline__ void prefetch_tile(uint4 (&kreg)[LD], uint4 (&vreg)[LD],
+__device__ __forceinline__ void prefetch_tile(u32x4_native (&kreg)[LD], u32x4_native (&vreg)[LD],
                                               const bf16_t* kbase, const bf16_t* vbase,
                                               const TileIter& t, int64_t tok_stride, int ld_row,
                                               int ld_col) {
@@ -63,20 +63,20 @@ __device__ __forceinline__ void prefetch_tile(uint4 (&kreg)[LD], uint4 (&vreg)[L
         int row = p * ROWS_PER_PASS + ld_row;
         if (row > nvalid - 1) row = nvalid - 1;
         const int64_t off = (int64_t)(t.start + t.t0 + row) * tok_stride + ld_col * 8;
-        kreg[p] = *reinterpret_cast<const uint4*>(kbase + off);
-        vreg[p] = *reinterpret_cast<const uint4*>(vbase + off);
+        kreg[p] = *reinterpret_cast<const u32x4_native*>(kbase + off);
+        vreg[p] = *reinterpret_cast<const u32x4_native*>(vbase + off);
     }
 }
 
 template <int LD, int ROWS_PER_PASS>
-__device__ __forceinline__ void stage_tile(const uint4 (&kreg)[LD], const uint4 (&vreg)[LD],
+__device__ __forceinline__ void stage_tile(const u32x4_native (&kreg)[LD], const u32x4_native (&vreg)[LD],
                                            bf16_t* Kb, bf16_t* Vb, int krow, int vrow, int ld_row,
                                            int ld_col) {
 #pragma unroll
     for (int p = 0; p < LD; ++p) {
         const int row = p * ROWS_PER_PASS + ld_row;
-        *reinterpret_cast<uint4*>(&Kb[row * krow + ld_col * 8]) = kreg[p];
-        *reinterpret_cast<uint4*>(&Vb[row * vrow + ld_col * 8]) = vreg[p];
+        *reinterpret_cast<u32x4_native*>(&Kb[row * krow + ld_col * 8]) = kreg[p];
+        *reinterpret_cast<u32x4_native*>(&Vb[row * vrow + ld_col * 8]) = vreg[p];
     }
 }
 
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
 
     // Global -> register prefetch of one tile (rows past the end of a segment are clamped
     // to its last row) and its later store to LDS.
-    uint4 kreg[LD], vreg[LD];
+    u32x4_native kreg[LD], vreg[LD];
     const int ld_row = tid / VPR, ld_col = tid % VPR;
     // per-lane offsets of the fragment reads
     const int k_frag_off = l32 * KROW + 8 * hh;
@@ -166,116 +166,129 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     const int l16 = lane & 15;
     const int v_frag_off = (hh * 4 + (l16 >> 2)) * VROW + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
 
-    prefetch_tile<LD, NT / VPR>(kreg, vreg, kbase, vbase, it, a.tok_stride, ld_row, ld_col);
+    // S^T = K Q^T of the tile in LDS buffer `BUF` (NV valid keys) and its scaled row max.
+    // sacc[qb][kb]: lane holds query l32, keys kb*32 + (i/4)*8 + hh*4 + i%4.
+    f32x16_t sacc[2][2];
+    float mx[2];
+#define FC_QK(BUF, NV)                                                                        \
+    {                                                                                         \
+        const bf16_t* Kb_ = Ks[BUF];                                                          \
+        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                    \
+            _Pragma("unroll") for (int st = 0; st < KS; ++st) {                               \
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(                       \
+                    &Kb_[kb * 32 * KROW + k_frag_off + 16 * st]);                             \
+                if (st == 0) {                                                                \
+                    f32x16_t z;                                                               \
+                    _Pragma("unroll") for (int i = 0; i < 16; ++i) z[i] = 0.f;                \
+                    sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], z, 0, 0, 0); \
+                    sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], z, 0, 0, 0); \
+                } else {                                                                      \
+                    sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], sacc[0][kb], 0, 0, 0); \
+                    sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], sacc[1][kb], 0, 0, 0); \
+                }                                                                             \
+            }                                                                                 \
+        }                                                                                     \
+        if ((NV) < BK) { /* ragged tail of a segment: mask the keys past its end */           \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                  \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i) {                              \
+                    const int key = kb * 32 + (i >> 2) * 8 + hh * 4 + (i & 3);                \
+                    if (key >= (NV)) { sacc[0][kb][i] = kNegBig; sacc[1][kb][i] = kNegBig; }  \
+                }                                                                             \
+        }                                                                                     \
+        _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                    \
+            float v = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);                                  \
+            _Pragma("unroll") for (int i = 1; i < 16; ++i)                                    \
+                v = fmaxf(v, fmaxf(sacc[qb][0][i], sacc[qb][1][i]));                          \
+            v = fmaxf(v, __shfl_xor(v, 32, FC_WAVE));                                         \
+            mx[qb] = v * c2;                                                                  \
+        }                                                                                     \
+    }
+    // Fetch the tile `it` points at into registers and step the iterator.
+#define FC_FETCH_NEXT()                                                                       \
+    {                                                                                         \
+        pending = !it.done;                                                                   \
+        nv_pending = (it.len - it.t0 < BK) ? it.len - it.t0 : BK;                             \
+        prefetch_tile<LD, NT / VPR>(kreg, vreg, kbase, vbase, it, a.tok_stride, ld_row, ld_col); \
+        if (pending) {                                                                        \
+            it.t0 += BK;                                                                      \
+            if (it.t0 >= it.len) next_segment(it);                                            \
+        }                                                                                     \
+    }
+
+    bool pending;
+    int nv_pending, nv_cur;
+    int buf = 0;
+    FC_FETCH_NEXT();                                                     // tile 0 -> registers
     stage_tile<LD, NT / VPR>(kreg, vreg, Ks[0], Vs[0], KROW, VROW, ld_row, ld_col);
     __syncthreads();
-    int buf = 0;
+    nv_cur = nv_pending;
+    FC_FETCH_NEXT();                                                     // tile 1 in flight
+    FC_QK(0, nv_cur);
 
-    while (!it.done) {
-        const int nvalid = (it.len - it.t0 < BK) ? it.len - it.t0 : BK;
-        it.t0 += BK;
-        if (it.t0 >= it.len) next_segment(it);
-        // next tile: in flight during the compute (unconditional: after the last tile the
-        // iterator points at a valid tile again and the loaded data is simply not used)
-        prefetch_tile<LD, NT / VPR>(kreg, vreg, kbase, vbase, it, a.tok_stride, ld_row, ld_col);
-
-        const bf16_t* Kb = Ks[buf];
-        const bf16_t* Vb = Vs[buf];
-
-        // ---- S^T = K Q^T : sacc[qb][kb], lane: query l32, keys kb*32 + (i/4)*8 + hh*4 + i%4
-        f32x16_t sacc[2][2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int st = 0; st < KS; ++st) {
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(
-                    &Kb[kb * 32 * KROW + k_frag_off + 16 * st]);
-                if (st == 0) {
-                    f32x16_t z;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) z[i] = 0.f;
-                    sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], z, 0, 0, 0);
-                    sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], z, 0, 0, 0);
-                } else {
-                    sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], sacc[0][kb], 0, 0, 0);
-                    sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], sacc[1][kb], 0, 0, 0);
-                }
-            }
-        }
-        if (nvalid < BK) {  // ragged tail of a segment: mask the keys past its end
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int key = kb * 32 + (i >> 2) * 8 + hh * 4 + (i & 3);
-                    if (key >= nvalid) { sacc[0][kb][i] = kNegBig; sacc[1][kb][i] = kNegBig; }
-                }
-        }
-
-        // ---- running max: raised (with a rescale of O and l) only when some row grew a lot
-        float mx[2];
+    // Outer loop: raise the running max (rescaling O and l) -- entered once at the start
+    // and then only when some row's max grew by more than 2^kRaise.  Inner loop: the
+    // steady state, in which O is touched by the matrix cores only.
+    for (;;) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            float v = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);
+            const float mnew = fmaxf(m[qb], mx[qb]);
+            const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
+            m[qb] = mnew;
+            lsum[qb] *= alpha;
 #pragma unroll
-            for (int i = 1; i < 16; ++i) v = fmaxf(v, fmaxf(sacc[qb][0][i], sacc[qb][1][i]));
-            v = fmaxf(v, __shfl_xor(v, 32, FC_WAVE));
-            mx[qb] = v * c2;
+            for (int dv = 0; dv < DVB; ++dv)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[qb][dv][i] *= alpha;
         }
-        if (__any((mx[0] > m[0] + kRaise) || (mx[1] > m[1] + kRaise))) {
+        bool finished = false;
+        do {
+            // ---- P^T = exp2(S^T c2 - m), packed to bf16 (B operand of the next product)
+            bf16x8_t pf[2][4];
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
-                const float mnew = fmaxf(m[qb], mx[qb]);
-                const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
-                m[qb] = mnew;
-                lsum[qb] *= alpha;
+                const float mneg = -m[qb];
+                float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
-                for (int dv = 0; dv < DVB; ++dv)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) o[qb][dv][i] *= alpha;
+                    for (int i = 0; i < 16; i += 2) {
+                        const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i], c2, mneg));
+                        const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 1], c2, mneg));
+                        ps0 += p0;
+                        ps1 += p1;
+                        pf[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)p0;
+                        pf[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)p1;
+                    }
+                lsum[qb] += ps0 + ps1;
             }
-        }
-
-        // ---- P^T = exp2(S^T c2 - m), packed to bf16 (B operand of the next product)
-        bf16x8_t pf[2][4];
+            // ---- O^T += V^T P^T : 16-key steps t (keys t*16 ..), value blocks dv
+            const bf16_t* Vb = Vs[buf];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float mneg = -m[qb];
-            float ps0 = 0.f, ps1 = 0.f;
+            for (int t = 0; t < 4; ++t) {
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i], c2, mneg));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 1], c2, mneg));
-                    ps0 += p0;
-                    ps1 += p1;
-                    pf[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)p0;
-                    pf[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)p1;
+                for (int dv = 0; dv < DVB; ++dv) {
+                    const bf16_t* vp = &Vb[t * 16 * VROW + v_frag_off + dv * 32];
+                    const s16x4_t lo = lds_read_tr(vp);
+                    const s16x4_t hi = lds_read_tr(vp + 8 * VROW);
+                    const s16x8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
+                    o[0][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[0][t], o[0][dv], 0, 0, 0);
+                    o[1][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1][t], o[1][dv], 0, 0, 0);
                 }
-            lsum[qb] += ps0 + ps1;
-        }
-
-        // ---- O^T += V^T P^T : 16-key steps t (keys t*16 ..), value blocks dv
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-#pragma unroll
-            for (int dv = 0; dv < DVB; ++dv) {
-                const bf16_t* vp = &Vb[t * 16 * VROW + v_frag_off + dv * 32];
-                const s16x4_t lo = lds_read_tr(vp);
-                const s16x4_t hi = lds_read_tr(vp + 8 * VROW);
-                const s16x8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
-                o[0][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[0][t], o[0][dv], 0, 0, 0);
-                o[1][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1][t], o[1][dv], 0, 0, 0);
             }
-        }
-
-        if (!it.done)                     // the prefetched tile goes to the other buffer
+            if (!pending) { finished = true; break; }
+            // ---- next tile: registers -> the other LDS buffer, one barrier per tile
             stage_tile<LD, NT / VPR>(kreg, vreg, Ks[buf ^ 1], Vs[buf ^ 1], KROW, VROW, ld_row, ld_col);
-        __syncthreads();
-        buf ^= 1;
+            __syncthreads();
+            buf ^= 1;
+            nv_cur = nv_pending;
+            FC_FETCH_NEXT();
+            FC_QK(buf, nv_cur);
+        } while (!__any((mx[0] > m[0] + kRaise) || (mx[1] > m[1] + kRaise)));
+        if (finished) break;
     }
+#undef FC_QK
+#undef FC_FETCH_NEXT
 
     // ---- epilogue: normalise, store O (bf16) and the row log-sum-exp
 #pragma unroll
