@@ -17,8 +17,11 @@
 //                 16 lanes x 4 keys), two loads per 8-key fragment.
 // The running max is only raised (and O rescaled) when some row's max grew by more than
 // 2^8, so the rescale is rare; until then P is bounded by 256, harmless in fp32 / bf16.
-// K/V tiles are fetched with 16-byte global loads one tile ahead of the compute and
-// double-buffered in LDS: one barrier per tile.
+// O += V P of tile j-1 is issued together with the exp2 / sum / pack of tile j, so the
+// matrix cores work while the vector ALU turns S into P (one wavefront per SIMD: nothing
+// else hides the vector work).  K/V tiles are fetched with 16-byte global loads one tile
+// ahead and live in a ring of three LDS buffers (tile j-1 still feeds O += V P while tile
+// j+1 is being written): one barrier per tile.
 // Work-groups are mapped so that the 32 compute units of one XCD work on the same head
 // and chunk at the same time and share the K/V stream through that XCD's L2.
 #include "fc_common.hpp"
@@ -108,8 +111,9 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, hh = lane >> 5;
 
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[2][BK * KROW];
-    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][BK * VROW];
+    constexpr int NBUF = 3;
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[NBUF][BK * KROW];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[NBUF][BK * VROW];
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[q = l32][16*step + 8*hh ..+8)
     bf16x8_t qf[2][KS];
@@ -215,22 +219,56 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
         }                                                                                     \
     }
 
+    // O^T += V^T P^T for the tile in V buffer VBUF: 16-key steps t, value blocks dv
+#define FC_PV(PP, VBUF)                                                                       \
+    {                                                                                         \
+        const bf16_t* Vb_ = (VBUF) + v_frag_off;                                              \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                       \
+            _Pragma("unroll") for (int dv = 0; dv < DVB; ++dv) {                              \
+                const bf16_t* vp = Vb_ + t * 16 * VROW + dv * 32;                             \
+                const s16x4_t lo = lds_read_tr(vp);                                           \
+                const s16x4_t hi = lds_read_tr(vp + 8 * VROW);                                \
+                const s16x8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);   \
+                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);                         \
+                o[0][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, PP[0][t], o[0][dv], 0, 0, 0); \
+                o[1][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, PP[1][t], o[1][dv], 0, 0, 0); \
+            }                                                                                 \
+        }                                                                                     \
+    }
+
     bool pending;
     int nv_pending, nv_cur;
-    int buf = 0;
+    bf16x8_t pprev[2][4];   // P of the previous tile, not yet multiplied into O
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pprev[qb][t][i] = (__bf16)0.f;
+    // buffer 2 plays "tile -1" in the first step: its V must be finite (P is zero there)
+    for (int i = tid; i < BK * VROW / 8; i += NT)
+        reinterpret_cast<uint4*>(Vs[2])[i] = make_uint4(0, 0, 0, 0);
+
     FC_FETCH_NEXT();                                                     // tile 0 -> registers
     stage_tile<LD, NT / VPR>(kreg, vreg, Ks[0], Vs[0], KROW, VROW, ld_row, ld_col);
     __syncthreads();
     nv_cur = nv_pending;
     FC_FETCH_NEXT();                                                     // tile 1 in flight
     FC_QK(0, nv_cur);
+    int b = 0, bprev = 2, bnext = 1;
 
     // Outer loop: raise the running max (rescaling O and l) -- entered once at the start
-    // and then only when some row's max grew by more than 2^kRaise.  Inner loop: the
-    // steady state, in which O is touched by the matrix cores only.
+    // and then only when some row's max grew by more than 2^kRaise.  The pending O += V P
+    // still belongs to the old scale: it is applied first and then emptied.
+    // Inner loop: the steady state, in which O is touched by the matrix cores only.
     for (;;) {
+        FC_PV(pprev, Vs[bprev])
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pprev[qb][t][i] = (__bf16)0.f;
             const float mnew = fmaxf(m[qb], mx[qb]);
             const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
             m[qb] = mnew;
@@ -242,8 +280,10 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
         }
         bool finished = false;
         do {
-            // ---- P^T = exp2(S^T c2 - m), packed to bf16 (B operand of the next product)
+            // ---- matrix cores: O += V P(j-1);  vector ALU: P(j) = exp2(S(j) c2 - m), row
+            //      sums, bf16 pack (B operand of the next tile's product)
             bf16x8_t pf[2][4];
+            FC_PV(pprev, Vs[bprev])
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
                 const float mneg = -m[qb];
@@ -261,32 +301,30 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
                     }
                 lsum[qb] += ps0 + ps1;
             }
-            // ---- O^T += V^T P^T : 16-key steps t (keys t*16 ..), value blocks dv
-            const bf16_t* Vb = Vs[buf];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-                for (int dv = 0; dv < DVB; ++dv) {
-                    const bf16_t* vp = &Vb[t * 16 * VROW + v_frag_off + dv * 32];
-                    const s16x4_t lo = lds_read_tr(vp);
-                    const s16x4_t hi = lds_read_tr(vp + 8 * VROW);
-                    const s16x8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
-                    o[0][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[0][t], o[0][dv], 0, 0, 0);
-                    o[1][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1][t], o[1][dv], 0, 0, 0);
+                for (int t = 0; t < 4; ++t) {
+                    // anchor: P must be computed here, next to the matrix-core work, not be
+                    // sunk to the loop latch where nothing would overlap it
+                    asm volatile("" : "+v"(pf[qb][t]));
+                    pprev[qb][t] = pf[qb][t];
                 }
-            }
             if (!pending) { finished = true; break; }
-            // ---- next tile: registers -> the other LDS buffer, one barrier per tile
-            stage_tile<LD, NT / VPR>(kreg, vreg, Ks[buf ^ 1], Vs[buf ^ 1], KROW, VROW, ld_row, ld_col);
+            // ---- next tile: registers -> LDS (that buffer's tile j-2 is fully consumed)
+            stage_tile<LD, NT / VPR>(kreg, vreg, Ks[bnext], Vs[bnext], KROW, VROW, ld_row, ld_col);
             __syncthreads();
-            buf ^= 1;
+            bprev = b;
+            b = bnext;
+            bnext = (bnext == NBUF - 1) ? 0 : bnext + 1;
             nv_cur = nv_pending;
             FC_FETCH_NEXT();
-            FC_QK(buf, nv_cur);
+            FC_QK(b, nv_cur);
         } while (!__any((mx[0] > m[0] + kRaise) || (mx[1] > m[1] + kRaise)));
         if (finished) break;
     }
+    FC_PV(pprev, Vs[b])                                                  // drain the pipeline
+#undef FC_PV
 #undef FC_QK
 #undef FC_FETCH_NEXT
 
