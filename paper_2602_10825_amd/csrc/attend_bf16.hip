@@ -15,8 +15,11 @@
 //   O^T += V^T P^T  A = V^T fragment read from the row-major V tile with the transposing
 //                 LDS load ds_read_b64_tr_b16 (each 16-lane group turns 4 keys x 16 dv into
 //                 16 lanes x 4 keys), two loads per 8-key fragment.
-// The running max is only raised (and O rescaled) when some row's max grew by more than
-// 2^8, so the rescale is rare; until then P is bounded by 256, harmless in fp32 / bf16.
+// The reference point m of the exponent is NOT the running row max: it is raised (and O, l
+// rescaled) only when some P of a tile exceeds 2^40, which the row sums reveal for free.
+// exp2(S c2 - m) then stays far inside the fp32 / bf16 exponent range, the final O / l is
+// unchanged, and the steady state carries no row-max reduction and no rescale at all.
+// The first tile always takes the raise path once (m starts at -1e30).
 // O += V P of tile j-1 is issued together with the exp2 / sum / pack of tile j, so the
 // matrix cores work while the vector ALU turns S into P (one wavefront per SIMD: nothing
 // else hides the vector work).  K/V tiles are fetched with 16-byte global loads one tile
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
                                       // load fall in disjoint bank quarters
     constexpr int VPR = D / 8;        // 16-byte vectors per K/V row
     constexpr int LD = BK * VPR / NT; // global loads per thread per tile (K, and again V)
-    constexpr float kRaise = 8.0f;    // raise the running max only past this many octaves
+    constexpr float kTooBig = 1.0995116e12f;  // 2^40: a row sum above this triggers a raise of m
 
     const int bid = blockIdx.x;
     const int xcd = bid % NXCD, slot = bid / NXCD;
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     const int l16 = lane & 15;
     const int v_frag_off = (hh * 4 + (l16 >> 2)) * VROW + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
 
-    // S^T = K Q^T of the tile in LDS buffer `BUF` (NV valid keys) and its scaled row max.
+    // S^T = K Q^T of the tile in LDS buffer `BUF` (NV valid keys).
     // sacc[qb][kb]: lane holds query l32, keys kb*32 + (i/4)*8 + hh*4 + i%4.
     f32x16_t sacc[2][2];
     float mx[2];
@@ -199,13 +202,31 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
                     if (key >= (NV)) { sacc[0][kb][i] = kNegBig; sacc[1][kb][i] = kNegBig; }  \
                 }                                                                             \
         }                                                                                     \
-        _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                    \
-            float v = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);                                  \
-            _Pragma("unroll") for (int i = 1; i < 16; ++i)                                    \
-                v = fmaxf(v, fmaxf(sacc[qb][0][i], sacc[qb][1][i]));                          \
-            v = fmaxf(v, __shfl_xor(v, 32, FC_WAVE));                                         \
-            mx[qb] = v * c2;                                                                  \
-        }                                                                                     \
+    }
+    // scaled row max of S (only needed when m has to be raised)
+#define FC_ROWMAX()                                                                           \
+    _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                        \
+        float v = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);                                      \
+        _Pragma("unroll") for (int i = 1; i < 16; ++i)                                        \
+            v = fmaxf(v, fmaxf(sacc[qb][0][i], sacc[qb][1][i]));                              \
+        v = fmaxf(v, __shfl_xor(v, 32, FC_WAVE));                                             \
+        mx[qb] = v * c2;                                                                      \
+    }
+    // P^T = exp2(S^T c2 - m) packed to bf16 (B operand of O^T += V^T P^T) and its row sums
+#define FC_EXP(PF, PS)                                                                        \
+    _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                        \
+        const float mneg = -m[qb];                                                            \
+        float ps0 = 0.f, ps1 = 0.f;                                                           \
+        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                      \
+            _Pragma("unroll") for (int i = 0; i < 16; i += 2) {                               \
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i], c2, mneg));     \
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 1], c2, mneg)); \
+                ps0 += p0;                                                                    \
+                ps1 += p1;                                                                    \
+                PF[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)p0;                                \
+                PF[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)p1;                          \
+            }                                                                                 \
+        PS[qb] = ps0 + ps1;                                                                   \
     }
     // Fetch the tile `it` points at into registers and step the iterator.
 #define FC_FETCH_NEXT()                                                                       \
@@ -237,8 +258,9 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     }
 
     bool pending;
-    int nv_pending, nv_cur;
+    int nv_pending, nv_cur = BK;
     bf16x8_t pprev[2][4];   // P of the previous tile, not yet multiplied into O
+    float psum[2] = {0.f, 0.f};
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -248,68 +270,38 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     // buffer 2 plays "tile -1" in the first step: its V must be finite (P is zero there)
     for (int i = tid; i < BK * VROW / 8; i += NT)
         reinterpret_cast<uint4*>(Vs[2])[i] = make_uint4(0, 0, 0, 0);
+    sacc[0][0] = sacc[0][1] = sacc[1][0] = sacc[1][1] = o[0][0];   // zeros (unused until tile 0)
 
     FC_FETCH_NEXT();                                                     // tile 0 -> registers
-    stage_tile<LD, NT / VPR>(kreg, vreg, Ks[0], Vs[0], KROW, VROW, ld_row, ld_col);
-    __syncthreads();
-    nv_cur = nv_pending;
-    FC_FETCH_NEXT();                                                     // tile 1 in flight
-    FC_QK(0, nv_cur);
-    int b = 0, bprev = 2, bnext = 1;
+    int b = 2, bprev = 1, bnext = 0;
+    bool first = true;
 
-    // Outer loop: raise the running max (rescaling O and l) -- entered once at the start
-    // and then only when some row's max grew by more than 2^kRaise.  The pending O += V P
-    // still belongs to the old scale: it is applied first and then emptied.
-    // Inner loop: the steady state, in which O is touched by the matrix cores only.
+    // Inner loop = steady state: stage the next tile, S = K Q^T, then O += V P(previous
+    // tile) on the matrix cores while the vector ALU turns S into P.  It is left when a row
+    // sum shows that m must be raised; the outer loop does that (true row max of the tile,
+    // rescale of O and l -- the pending P of the previous tile has already been applied in
+    // the old scale --, P recomputed) and re-enters.
     for (;;) {
-        FC_PV(pprev, Vs[bprev])
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) pprev[qb][t][i] = (__bf16)0.f;
-            const float mnew = fmaxf(m[qb], mx[qb]);
-            const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
-            m[qb] = mnew;
-            lsum[qb] *= alpha;
-#pragma unroll
-            for (int dv = 0; dv < DVB; ++dv)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[qb][dv][i] *= alpha;
-        }
-        bool finished = false;
-        do {
-            // ---- matrix cores: O += V P(j-1);  vector ALU: P(j) = exp2(S(j) c2 - m), row
-            //      sums, bf16 pack (B operand of the next tile's product)
-            bf16x8_t pf[2][4];
-            FC_PV(pprev, Vs[bprev])
+        if (!first) {
+            FC_ROWMAX()
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
-                const float mneg = -m[qb];
-                float ps0 = 0.f, ps1 = 0.f;
+                const float mnew = fmaxf(m[qb], mx[qb]);
+                const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
+                m[qb] = mnew;
+                lsum[qb] *= alpha;
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int dv = 0; dv < DVB; ++dv)
 #pragma unroll
-                    for (int i = 0; i < 16; i += 2) {
-                        const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i], c2, mneg));
-                        const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 1], c2, mneg));
-                        ps0 += p0;
-                        ps1 += p1;
-                        pf[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)p0;
-                        pf[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)p1;
-                    }
-                lsum[qb] += ps0 + ps1;
+                    for (int i = 0; i < 16; ++i) o[qb][dv][i] *= alpha;
             }
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    // anchor: P must be computed here, next to the matrix-core work, not be
-                    // sunk to the loop latch where nothing would overlap it
-                    asm volatile("" : "+v"(pf[qb][t]));
-                    pprev[qb][t] = pf[qb][t];
-                }
+            FC_EXP(pprev, psum)
+        }
+        first = false;
+        bool finished = false;
+        do {
+            lsum[0] += psum[0];
+            lsum[1] += psum[1];
             if (!pending) { finished = true; break; }
             // ---- next tile: registers -> LDS (that buffer's tile j-2 is fully consumed)
             stage_tile<LD, NT / VPR>(kreg, vreg, Ks[bnext], Vs[bnext], KROW, VROW, ld_row, ld_col);
@@ -320,12 +312,28 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
             nv_cur = nv_pending;
             FC_FETCH_NEXT();
             FC_QK(b, nv_cur);
-        } while (!__any((mx[0] > m[0] + kRaise) || (mx[1] > m[1] + kRaise)));
+            // ---- matrix cores: O += V P(j-1);  vector ALU: P(j) = exp2(S(j) c2 - m), row
+            //      sums, bf16 pack
+            bf16x8_t pf[2][4];
+            FC_PV(pprev, Vs[bprev])
+            FC_EXP(pf, psum)
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    // anchor: P must be computed here, next to the matrix-core work, not be
+                    // sunk to the loop latch where nothing would overlap it
+                    asm volatile("" : "+v"(pf[qb][t]));
+                    pprev[qb][t] = pf[qb][t];
+                }
+        } while (!__any((psum[0] > kTooBig) || (psum[1] > kTooBig)));
         if (finished) break;
     }
     FC_PV(pprev, Vs[b])                                                  // drain the pipeline
 #undef FC_PV
 #undef FC_QK
+#undef FC_ROWMAX
+#undef FC_EXP
 #undef FC_FETCH_NEXT
 
     // ---- epilogue: normalise, store O (bf16) and the row log-sum-exp
