@@ -195,6 +195,13 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
                 }                                                                             \
             }                                                                                 \
         }                                                                                     \
+        /* issue order: 8 fragment reads ahead of the matrix-core chain that uses them */     \
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);                                    \
+        _Pragma("unroll") for (int g = 0; g < (4 * KS - 16) / 4; ++g) {                       \
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);                                \
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                \
+        }                                                                                     \
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);                                   \
         if ((NV) < BK) { /* ragged tail of a segment: mask the keys past its end */           \
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                  \
                 _Pragma("unroll") for (int i = 0; i < 16; ++i) {                              \
@@ -326,6 +333,13 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
                     asm volatile("" : "+v"(pf[qb][t]));
                     pprev[qb][t] = pf[qb][t];
                 }
+            // issue order: V fragments are read 4 fragments (8 loads) ahead of their use
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+            for (int f = 0; f < 4 * DVB; ++f) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                if (f + 4 < 4 * DVB) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
         } while (!__any((psum[0] > kTooBig) || (psum[1] > kTooBig)));
         if (finished) break;
     }
