@@ -36,9 +36,11 @@ typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
+#ifndef FC_ATTEND_QB
+#define FC_ATTEND_QB 1
+#endif
 constexpr int BQ = 256;      // query rows per workgroup
 constexpr int BK = 64;       // keys per tile
-constexpr int NT = 256;      // threads
 constexpr int NXCD = 8;
 constexpr float kNegBig = -1.0e30f;
 
@@ -86,8 +88,12 @@ __device__ __forceinline__ void stage_tile(const u32x4_native (&kreg)[LD], const
     }
 }
 
-template <int D>
-__global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int tiles, int per) {
+// QB = 32-row query blocks per wavefront: 2 -> 4 wavefronts of 64 rows (one per SIMD, 512
+// registers each), 1 -> 8 wavefronts of 32 rows (two per SIMD, 256 registers each).
+template <int D, int QB>
+__global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAttendArgs a, int tiles,
+                                                                            int per) {
+    constexpr int NT = 64 * (BQ / (32 * QB));
     constexpr int KS = D / 16;        // contraction steps of Q K^T
     constexpr int DVB = D / 32;       // 32-wide blocks of the value dimension
     constexpr int KROW = D + 8;       // padded K row (bf16): 16-byte fragment reads of 16
@@ -119,11 +125,11 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     __shared__ __attribute__((aligned(16))) bf16_t Vs[NBUF][BK * VROW];
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[q = l32][16*step + 8*hh ..+8)
-    bf16x8_t qf[2][KS];
-    int row_in_chunk[2];
+    bf16x8_t qf[QB][KS];
+    int row_in_chunk[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        int rc = tile * BQ + wave * 64 + qb * 32 + l32;
+    for (int qb = 0; qb < QB; ++qb) {
+        int rc = tile * BQ + wave * (32 * QB) + qb * 32 + l32;
         row_in_chunk[qb] = rc;
         if (rc > a.L_c - 1) rc = a.L_c - 1;
         const bf16_t* qp = (const bf16_t*)a.q + (((int64_t)r * a.L_c + rc) * a.H_q + h) * D + 8 * hh;
@@ -132,15 +138,16 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
             qf[qb][st] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * st);
     }
 
-    f32x16_t o[2][DVB];
+    f32x16_t o[QB][DVB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int dv = 0; dv < DVB; ++dv)
 #pragma unroll
             for (int i = 0; i < 16; ++i) o[qb][dv][i] = 0.f;
-    float m[2] = {kNegBig, kNegBig};
-    float lsum[2] = {0.f, 0.f};
+    float m[QB], lsum[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) { m[qb] = kNegBig; lsum[qb] = 0.f; }
     const float c2 = a.scale * 1.4426950408889634f;
 
     const bf16_t* kbase = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
@@ -175,44 +182,46 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
 
     // S^T = K Q^T of the tile in LDS buffer `BUF` (NV valid keys).
     // sacc[qb][kb]: lane holds query l32, keys kb*32 + (i/4)*8 + hh*4 + i%4.
-    f32x16_t sacc[2][2];
-    float mx[2];
+    f32x16_t sacc[QB][2];
+    float mx[QB];
 #define FC_QK(BUF, NV)                                                                        \
     {                                                                                         \
         const bf16_t* Kb_ = Ks[BUF];                                                          \
-        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                    \
-            _Pragma("unroll") for (int st = 0; st < KS; ++st) {                               \
+        _Pragma("unroll") for (int st = 0; st < KS; ++st) {                                   \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) { /* 2*QB independent chains */  \
                 const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(                       \
                     &Kb_[kb * 32 * KROW + k_frag_off + 16 * st]);                             \
-                if (st == 0) {                                                                \
-                    f32x16_t z;                                                               \
-                    _Pragma("unroll") for (int i = 0; i < 16; ++i) z[i] = 0.f;                \
-                    sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], z, 0, 0, 0); \
-                    sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], z, 0, 0, 0); \
-                } else {                                                                      \
-                    sacc[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], sacc[0][kb], 0, 0, 0); \
-                    sacc[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][st], sacc[1][kb], 0, 0, 0); \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                           \
+                    if (st == 0) {                                                            \
+                        f32x16_t z;                                                           \
+                        _Pragma("unroll") for (int i = 0; i < 16; ++i) z[i] = 0.f;            \
+                        sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][st], z, 0, 0, 0); \
+                    } else {                                                                  \
+                        sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][st], sacc[qb][kb], 0, 0, 0); \
+                    }                                                                         \
                 }                                                                             \
             }                                                                                 \
         }                                                                                     \
         /* issue order: 8 fragment reads ahead of the matrix-core chain that uses them */     \
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);                                    \
-        _Pragma("unroll") for (int g = 0; g < (4 * KS - 16) / 4; ++g) {                       \
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);                                \
+        _Pragma("unroll") for (int g = 0; g < (2 * KS - 8) / 2; ++g) {                        \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2 * QB, 0);                           \
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                \
         }                                                                                     \
-        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);                                   \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8 * QB, 0);                               \
         if ((NV) < BK) { /* ragged tail of a segment: mask the keys past its end */           \
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                  \
                 _Pragma("unroll") for (int i = 0; i < 16; ++i) {                              \
                     const int key = kb * 32 + (i >> 2) * 8 + hh * 4 + (i & 3);                \
-                    if (key >= (NV)) { sacc[0][kb][i] = kNegBig; sacc[1][kb][i] = kNegBig; }  \
+                    if (key >= (NV)) {                                                        \
+                        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) sacc[qb][kb][i] = kNegBig; \
+                    }                                                                         \
                 }                                                                             \
         }                                                                                     \
     }
     // scaled row max of S (only needed when m has to be raised)
 #define FC_ROWMAX()                                                                           \
-    _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                        \
+    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                        \
         float v = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);                                      \
         _Pragma("unroll") for (int i = 1; i < 16; ++i)                                        \
             v = fmaxf(v, fmaxf(sacc[qb][0][i], sacc[qb][1][i]));                              \
@@ -221,7 +230,7 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     }
     // P^T = exp2(S^T c2 - m) packed to bf16 (B operand of O^T += V^T P^T) and its row sums
 #define FC_EXP(PF, PS)                                                                        \
-    _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                        \
+    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                        \
         const float mneg = -m[qb];                                                            \
         float ps0 = 0.f, ps1 = 0.f;                                                           \
         _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                      \
@@ -258,18 +267,20 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
                 const s16x4_t hi = lds_read_tr(vp + 8 * VROW);                                \
                 const s16x8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);   \
                 const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);                         \
-                o[0][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, PP[0][t], o[0][dv], 0, 0, 0); \
-                o[1][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, PP[1][t], o[1][dv], 0, 0, 0); \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                             \
+                    o[qb][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, PP[qb][t], o[qb][dv], 0, 0, 0); \
             }                                                                                 \
         }                                                                                     \
     }
 
     bool pending;
     int nv_pending, nv_cur = BK;
-    bf16x8_t pprev[2][4];   // P of the previous tile, not yet multiplied into O
-    float psum[2] = {0.f, 0.f};
+    bf16x8_t pprev[QB][4];   // P of the previous tile, not yet multiplied into O
+    float psum[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb) psum[qb] = 0.f;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -277,7 +288,8 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
     // buffer 2 plays "tile -1" in the first step: its V must be finite (P is zero there)
     for (int i = tid; i < BK * VROW / 8; i += NT)
         reinterpret_cast<uint4*>(Vs[2])[i] = make_uint4(0, 0, 0, 0);
-    sacc[0][0] = sacc[0][1] = sacc[1][0] = sacc[1][1] = o[0][0];   // zeros (unused until tile 0)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) sacc[qb][0] = sacc[qb][1] = o[0][0];   // zeros (unused until tile 0)
 
     FC_FETCH_NEXT();                                                     // tile 0 -> registers
     int b = 2, bprev = 1, bnext = 0;
@@ -292,7 +304,7 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
         if (!first) {
             FC_ROWMAX()
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
+            for (int qb = 0; qb < QB; ++qb) {
                 const float mnew = fmaxf(m[qb], mx[qb]);
                 const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
                 m[qb] = mnew;
@@ -306,9 +318,10 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
         }
         first = false;
         bool finished = false;
+        bool raise = false;
         do {
-            lsum[0] += psum[0];
-            lsum[1] += psum[1];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) lsum[qb] += psum[qb];
             if (!pending) { finished = true; break; }
             // ---- next tile: registers -> LDS (that buffer's tile j-2 is fully consumed)
             stage_tile<LD, NT / VPR>(kreg, vreg, Ks[bnext], Vs[bnext], KROW, VROW, ld_row, ld_col);
@@ -321,11 +334,11 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
             FC_QK(b, nv_cur);
             // ---- matrix cores: O += V P(j-1);  vector ALU: P(j) = exp2(S(j) c2 - m), row
             //      sums, bf16 pack
-            bf16x8_t pf[2][4];
+            bf16x8_t pf[QB][4];
             FC_PV(pprev, Vs[bprev])
             FC_EXP(pf, psum)
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     // anchor: P must be computed here, next to the matrix-core work, not be
@@ -337,10 +350,14 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
             __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
             for (int f = 0; f < 4 * DVB; ++f) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
                 if (f + 4 < 4 * DVB) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             }
-        } while (!__any((psum[0] > kTooBig) || (psum[1] > kTooBig)));
+            bool too_big = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) too_big = too_big || (psum[qb] > kTooBig);
+            raise = __any(too_big);
+        } while (!raise);
         if (finished) break;
     }
     FC_PV(pprev, Vs[b])                                                  // drain the pipeline
@@ -352,7 +369,7 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
 
     // ---- epilogue: normalise, store O (bf16) and the row log-sum-exp
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const float ltot = lsum[qb] + __shfl_xor(lsum[qb], 32, FC_WAVE);
         const float inv = 1.0f / ltot;
         if (row_in_chunk[qb] < a.L_c) {
@@ -380,14 +397,16 @@ __global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int til
 }  // namespace
 
 int fc_launch_attend_bf16(const FcAttendArgs& a, hipStream_t s) {
+    constexpr int QB = FC_ATTEND_QB;
+    constexpr int NT = 64 * (BQ / (32 * QB));
     const int tiles = (a.L_c + BQ - 1) / BQ;
     const int items = a.H_q * tiles;
     const int per = (items + NXCD - 1) / NXCD;
     const dim3 grid((unsigned)(NXCD * per * a.A));
     if (a.d == 128)
-        attend_bf16_kernel<128><<<grid, NT, 0, s>>>(a, tiles, per);
+        attend_bf16_kernel<128, QB><<<grid, NT, 0, s>>>(a, tiles, per);
     else if (a.d == 64)
-        attend_bf16_kernel<64><<<grid, NT, 0, s>>>(a, tiles, per);
+        attend_bf16_kernel<64, QB><<<grid, NT, 0, s>>>(a, tiles, per);
     else
         return FC_UNSUPPORTED;
     FC_LAUNCH_CHECK();
