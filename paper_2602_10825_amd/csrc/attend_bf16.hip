@@ -117,7 +117,7 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
     const int hk = h / (a.H_q / a.H_k);
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave: scalar
     const int l32 = lane & 31, hh = lane >> 5;
 
     constexpr int NBUF = 3;
@@ -331,7 +331,11 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
             bnext = (bnext == NBUF - 1) ? 0 : bnext + 1;
             nv_cur = nv_pending;
             FC_FETCH_NEXT();
+            // The wavefront in its matrix-core-only phase outranks its SIMD sibling that is
+            // in the mixed phase: the sibling's vector work fills the gaps, and the two
+            // reach the next barrier closer together.
             FC_QK(b, nv_cur);
+            __builtin_amdgcn_s_setprio(2);
             // ---- matrix cores: O += V P(j-1);  vector ALU: P(j) = exp2(S(j) c2 - m), row
             //      sums, bf16 pack
             bf16x8_t pf[QB][4];
@@ -353,6 +357,7 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
                 __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
                 if (f + 4 < 4 * DVB) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             }
+            __builtin_amdgcn_s_setprio(0);
             bool too_big = false;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) too_big = too_big || (psum[qb] > kTooBig);
