@@ -8,8 +8,9 @@
 //                  linear-time form of the diagonal-zeroed column mean of Eq. (11)
 //   score_select   per head: softmax over r (Eq. (11)), max-pooled importance (Eq. (10)),
 //                  score (Eq. (12)) -> order-preserving 64-bit keys; radix select of the
-//                  budget-th largest key; ordered compaction of the kept positions
-//                  (ties: lower position wins; output ascending)
+//                  budget-th largest key, started at the most significant bit in which
+//                  the keys differ and finished on the few candidates left, in LDS; ordered
+//                  compaction of the kept positions (ties: lower position wins; ascending)
 //   gather_rows / copy_back   move kept K and V rows to positions [0, budget)
 // A 16-lane group owns one token row in the two passes over K (16-byte loads, a full
 // row per group), so a token's values never depend on where it sits in the launch.
@@ -93,20 +94,38 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
     }
 }
 
+// s = sum over blocks of the partial sums, in a fixed order: thread (slice, e) adds the
+// partials b = slice, slice + SL, ... ; the SL slice sums are then added in slice order.
 template <int D>
-__global__ void sum_partials_kernel(const double* __restrict__ psum, int nblk,
-                                    double* __restrict__ ssum) {
-    const int h = blockIdx.x, e = threadIdx.x;
+__global__ __launch_bounds__(1024) void sum_partials_kernel(const double* __restrict__ psum,
+                                                            int nblk, double* __restrict__ ssum) {
+    constexpr int SL = 1024 / D;
+    const int h = blockIdx.x, e = threadIdx.x % D, sl = threadIdx.x / D;
+    const double* p = psum + (int64_t)h * nblk * D + e;
     double t = 0.0;
-    for (int b = 0; b < nblk; ++b) t += psum[((int64_t)h * nblk + b) * D + e];
-    ssum[h * D + e] = t;
+    int b = sl;
+    for (; b + 3 * SL < nblk; b += 4 * SL) {
+        const double v0 = p[(int64_t)b * D], v1 = p[(int64_t)(b + SL) * D];
+        const double v2 = p[(int64_t)(b + 2 * SL) * D], v3 = p[(int64_t)(b + 3 * SL) * D];
+        t += v0; t += v1; t += v2; t += v3;
+    }
+    for (; b < nblk; b += SL) t += p[(int64_t)b * D];
+    __shared__ double sh[SL][D];
+    sh[sl][e] = t;
+    __syncthreads();
+    if (sl == 0) {
+        double tot = 0.0;
+#pragma unroll
+        for (int k = 0; k < SL; ++k) tot += sh[k][e];
+        ssum[h * D + e] = tot;
+    }
 }
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
     const double2* __restrict__ tokinfo, const double* __restrict__ ssum,
-    double* __restrict__ r) {
+    double* __restrict__ r, double* __restrict__ pmax) {
     constexpr int EL = D / 16;
     const int h = blockIdx.y;
     const int g = threadIdx.x / 16, u = threadIdx.x % 16;
@@ -115,6 +134,7 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
 #pragma unroll
     for (int e = 0; e < EL; ++e) s[e] = ssum[h * D + u * EL + e];
     const double dL = (double)L;
+    double rmax = -1.0e300;
     for (int j = blockIdx.x * kGroups + g; j < L; j += gridDim.x * kGroups) {
         double x[EL];
         load_slice<T, D>(base + (int64_t)j * tok_stride, u, x);
@@ -124,8 +144,19 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
         dot = group_sum(dot);
         if (u == 0) {
             const double2 ti = tokinfo[(int64_t)h * L + j];
-            r[(int64_t)h * L + j] = (dot * ti.x - ti.y) / dL;
+            const double rj = (dot * ti.x - ti.y) / dL;
+            r[(int64_t)h * L + j] = rj;
+            rmax = fmax(rmax, rj);
         }
+    }
+    __shared__ double shm[kGroups];
+    if (u == 0) shm[g] = rmax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double m = shm[0];
+#pragma unroll
+        for (int k = 1; k < kGroups; ++k) m = fmax(m, shm[k]);
+        pmax[(int64_t)h * gridDim.x + blockIdx.x] = m;
     }
 }
 
@@ -160,84 +191,245 @@ __device__ __forceinline__ uint64_t score_key(double score) {
     return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
 }
 
+constexpr int kDigitBits = 11;
+constexpr int kBins = 1 << kDigitBits;
+constexpr int kCand = 4096;   // candidates resolved in LDS
+constexpr int kUnroll = 8;    // independent loads in flight per thread in the selection scans
+
+__device__ __forceinline__ uint64_t block_reduce_u64(uint64_t v, bool want_max, uint64_t* sh) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint64_t w = (uint64_t)__shfl_xor((long long)v, o, FC_WAVE);
+        v = want_max ? (w > v ? w : v) : (w < v ? w : v);
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x / FC_WAVE] = v;
+    __syncthreads();
+    uint64_t m = sh[0];
+    for (int k = 1; k < kSelThreads / FC_WAVE; ++k) m = want_max ? (sh[k] > m ? sh[k] : m) : (sh[k] < m ? sh[k] : m);
+    return m;
+}
+
+// From a histogram of `nb` <= 2048 bins (counts of the current candidates by digit), find the
+// bin that holds the `need`-th largest candidate and the number of candidates in higher
+// bins.  All 1024 threads take part: thread t owns the two bins nb-1-2t and nb-2-2t, a block
+// scan in descending bin order gives the count above each, and the one thread whose bin
+// straddles `need` publishes the answer.  (A single thread walking the bins would pay one
+// LDS round trip per bin.)
+__device__ __forceinline__ void pick_bin_parallel(const uint32_t* hist, int nb, uint32_t need,
+                                                  uint32_t* wsum, uint64_t prefix, int shift,
+                                                  uint64_t* out_prefix, uint32_t* out_need,
+                                                  uint32_t* out_count) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid / FC_WAVE;
+    const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
+    const uint32_t h0 = (b0 >= 0) ? hist[b0] : 0u;
+    const uint32_t h1 = (b1 >= 0) ? hist[b1] : 0u;
+    uint32_t inc = h0 + h1;   // inclusive scan over threads (= descending bins)
+#pragma unroll
+    for (int o = 1; o < FC_WAVE; o <<= 1) {
+        const uint32_t t = __shfl_up(inc, o, FC_WAVE);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    uint32_t above = inc - (h0 + h1);
+    for (int w = 0; w < wave; ++w) above += wsum[w];
+    if (b0 >= 0 && above < need && need <= above + h0) {
+        *out_prefix = prefix | ((uint64_t)b0 << shift);
+        *out_need = need - above;
+        *out_count = h0;
+    } else if (b1 >= 0 && above + h0 < need && need <= above + h0 + h1) {
+        *out_prefix = prefix | ((uint64_t)b1 << shift);
+        *out_need = need - above - h0;
+        *out_count = h1;
+    }
+}
+
+// Histogram increment that survives skew: the digits most lanes of a wavefront share are
+// counted once per wavefront (up to four rounds of leader election); the rest go one by one.
+__device__ __forceinline__ void hist_add(uint32_t* hist, bool in, uint32_t dgt) {
+    uint64_t act = __ballot(in);
+#pragma unroll 1
+    for (int round = 0; round < 4 && act; ++round) {
+        const int leader = __ffsll((long long)act) - 1;
+        const uint32_t d0 = __shfl(dgt, leader, FC_WAVE);
+        const uint64_t same = __ballot(in && dgt == d0);
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+        in = in && (dgt != d0);
+        act &= ~same;
+    }
+    if (in) atomicAdd(&hist[dgt], 1u);
+}
+
+// Append `k` to an LDS list from the lanes with `take`; one counter update per wavefront.
+__device__ __forceinline__ void list_append(uint64_t* list, uint32_t* counter, bool take, uint64_t k) {
+    const uint64_t m = __ballot(take);
+    if (m == 0) return;
+    const int lane = threadIdx.x & 63;
+    const int leader = __ffsll((long long)m) - 1;
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+    base = __shfl(base, leader, FC_WAVE);
+    if (take) list[base + __popcll(m & ((1ull << lane) - 1ull))] = k;
+}
+
 __global__ __launch_bounds__(kSelThreads) void score_select_kernel(
-    const double* __restrict__ r_all, const float* __restrict__ mass_all, int L, int budget,
-    int pool_k, double lambda, uint64_t* __restrict__ keys_all, int32_t* __restrict__ kept_all) {
+    const double* __restrict__ r_all, const float* __restrict__ mass_all,
+    const double* __restrict__ pmax_all, int nblk, int L, int budget, int pool_k, double lambda,
+    double* __restrict__ etmp_all, uint64_t* __restrict__ keys_all, int32_t* __restrict__ kept_all) {
     const int h = blockIdx.x;
     const int tid = threadIdx.x;
     const double* r = r_all + (int64_t)h * L;
     const float* mass = mass_all + (int64_t)h * L;
+    double* etmp = etmp_all + (int64_t)h * L;
     uint64_t* keys = keys_all + (int64_t)h * L;
     int32_t* kept = kept_all + (int64_t)h * budget;
 
     __shared__ double shd[kSelThreads];
-    __shared__ uint32_t hist[256];
+    __shared__ uint64_t shu[kSelThreads / FC_WAVE];
+    __shared__ uint32_t hist[kBins];
+    __shared__ uint64_t cand[kCand];
     __shared__ uint32_t wtot[2][kSelThreads / FC_WAVE];
     __shared__ uint64_t sh_prefix;
-    __shared__ uint32_t sh_need;
+    __shared__ uint32_t sh_need, sh_count, sh_ncand;
 
-    // Eq. (11): softmax over the token index of r
+    // Eq. (11): softmax over the token index of r.  max r comes from the block maxima of
+    // the pass that produced r.
     double mx = -1.0e300;
-    for (int j = tid; j < L; j += kSelThreads) mx = fmax(mx, r[j]);
+    for (int i = tid; i < nblk; i += kSelThreads) mx = fmax(mx, pmax_all[(int64_t)h * nblk + i]);
     mx = block_max_d(mx, shd);
+    // All scans below fetch kUnroll independent elements per thread before using them: one
+    // block per head is latency-bound otherwise.
     double z = 0.0;
-    for (int j = tid; j < L; j += kSelThreads) z += exp(r[j] - mx);
+    for (int base = 0; base < L; base += kSelThreads * kUnroll) {
+        double rv[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = base + u * kSelThreads + tid;
+            rv[u] = (j < L) ? r[j] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = base + u * kSelThreads + tid;
+            if (j < L) {
+                const double e = exp(rv[u] - mx);
+                etmp[j] = e;
+                z += e;
+            }
+        }
+    }
     z = block_sum_d(z, shd);
 
-    // Eq. (10) + Eq. (12) -> sortable keys
+    // Eq. (10) + Eq. (12) -> sortable keys; their min and max bound the bits that matter
     const int half = pool_k / 2;
-    for (int j = tid; j < L; j += kSelThreads) {
-        const int lo = (j - half > 0) ? j - half : 0;
-        const int hi = (j + half < L - 1) ? j + half : L - 1;
-        float imp = mass[lo];
-        for (int u = lo + 1; u <= hi; ++u) imp = fmaxf(imp, mass[u]);
-        const double red = exp(r[j] - mx) / z;
-        const double a = lambda * (double)imp;
-        const double b = (1.0 - lambda) * red;
-        keys[j] = score_key(a - b);
-    }
-    __syncthreads();
-
-    // radix select: the budget-th largest key, 8 bits per pass from the top
-    uint64_t prefix = 0;
-    uint32_t need = (uint32_t)budget;
-    for (int shift = 56; shift >= 0; shift -= 8) {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
-        const uint64_t himask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
-        for (int j0 = 0; j0 < L; j0 += kSelThreads) {
-            const int j = j0 + tid;
-            const bool in = (j < L) && ((keys[j] & himask) == prefix);
-            const uint32_t dgt = in ? (uint32_t)((keys[j] >> shift) & 255u) : 0u;
-            // wave-aggregate the common case of one shared digit
-            const uint64_t act = __ballot(in);
-            if (act) {
-                const int leader = __ffsll((long long)act) - 1;
-                const uint32_t d0 = __shfl(dgt, leader, FC_WAVE);
-                const uint64_t same = __ballot(in && dgt == d0);
-                if (same == act) {
-                    if ((tid & 63) == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(act));
-                } else if (in) {
-                    atomicAdd(&hist[dgt], 1u);
+    uint64_t kmin = ~0ull, kmax = 0ull;
+    for (int base = 0; base < L; base += kSelThreads * kUnroll) {
+        double ev[kUnroll];
+        float imp[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = base + u * kSelThreads + tid;
+            ev[u] = (j < L) ? etmp[j] : 0.0;
+            imp[u] = (j < L) ? mass[j] : 0.f;
+        }
+        for (int d = 1; d <= half; ++d) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int j = base + u * kSelThreads + tid;
+                if (j < L) {
+                    const float lo = (j - d >= 0) ? mass[j - d] : imp[u];
+                    const float hi = (j + d < L) ? mass[j + d] : imp[u];
+                    imp[u] = fmaxf(imp[u], fmaxf(lo, hi));
                 }
             }
         }
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t cum = 0;
-            int b = 255;
-            for (; b > 0; --b) {
-                if (cum + hist[b] >= need) break;
-                cum += hist[b];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = base + u * kSelThreads + tid;
+            if (j < L) {
+                const double red = ev[u] / z;
+                const double a = lambda * (double)imp[u];
+                const double b = (1.0 - lambda) * red;
+                const uint64_t k = score_key(a - b);
+                keys[j] = k;
+                kmin = k < kmin ? k : kmin;
+                kmax = k > kmax ? k : kmax;
             }
-            sh_prefix = prefix | ((uint64_t)b << shift);
-            sh_need = need - cum;
         }
-        __syncthreads();
-        prefix = sh_prefix;
-        need = sh_need;
     }
-    const uint64_t thr = prefix;  // budget-th largest key; keep `need` of its copies
+    kmin = block_reduce_u64(kmin, false, shu);
+    kmax = block_reduce_u64(kmax, true, shu);
+    __syncthreads();
+
+    // Radix select of the budget-th largest key.  All keys agree above bit `top`.
+    uint64_t thr;
+    uint32_t need = (uint32_t)budget;
+    const uint64_t diff = kmin ^ kmax;
+    if (diff == 0) {
+        thr = kmax;   // every score is the same: keep the first `budget` positions
+    } else {
+        const int top = 63 - __clzll((long long)diff);
+        int rem = top + 1;                                         // undecided low bits
+        uint64_t prefix = (rem == 64) ? 0ull : (kmax >> rem) << rem;
+        bool in_lds = false;
+        uint32_t ncand = 0;
+        while (rem > 0) {
+            const int w = in_lds ? (rem < 8 ? rem : 8) : (rem < kDigitBits ? rem : kDigitBits);
+            const int shift = rem - w;
+            const int nb = 1 << w;
+            for (int i = tid; i < nb; i += kSelThreads) hist[i] = 0;
+            __syncthreads();
+            const uint64_t himask = (rem == 64) ? 0ull : (~0ull << rem);
+            if (in_lds) {
+                for (uint32_t i0 = 0; i0 < ncand; i0 += kSelThreads) {
+                    const uint32_t i = i0 + tid;
+                    const uint64_t k = (i < ncand) ? cand[i] : ~prefix;
+                    hist_add(hist, i < ncand && (k & himask) == prefix, (uint32_t)(k >> shift) & (nb - 1));
+                }
+            } else {
+                for (int base = 0; base < L; base += kSelThreads * kUnroll) {
+                    uint64_t kv[kUnroll];
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u) {
+                        const int j = base + u * kSelThreads + tid;
+                        kv[u] = (j < L) ? keys[j] : ~prefix;   // padding never matches the prefix
+                    }
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u)
+                        hist_add(hist, (kv[u] & himask) == prefix && base + u * kSelThreads + tid < L,
+                                 (uint32_t)(kv[u] >> shift) & (nb - 1));
+                }
+            }
+            __syncthreads();
+            if (tid == 0) sh_ncand = 0;
+            pick_bin_parallel(hist, nb, need, wtot[0], prefix, shift, &sh_prefix, &sh_need, &sh_count);
+            __syncthreads();
+            prefix = sh_prefix;
+            need = sh_need;
+            rem = shift;
+            // few candidates left: pull them into LDS and finish there
+            if (!in_lds && rem > 0 && sh_count <= (uint32_t)kCand) {
+                const uint64_t hm = ~0ull << rem;
+                for (int base = 0; base < L; base += kSelThreads * kUnroll) {
+                    uint64_t kv[kUnroll];
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u) {
+                        const int j = base + u * kSelThreads + tid;
+                        kv[u] = (j < L) ? keys[j] : 0ull;
+                    }
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u)
+                        list_append(cand, &sh_ncand,
+                                    (kv[u] & hm) == prefix && base + u * kSelThreads + tid < L, kv[u]);
+                }
+                __syncthreads();
+                ncand = sh_ncand;
+                in_lds = true;
+            }
+        }
+        thr = prefix;
+    }
 
     // ordered compaction: position = #greater before + min(#equal before, need)
     uint32_t run_gt = 0, run_eq = 0;
@@ -245,12 +437,14 @@ __global__ __launch_bounds__(kSelThreads) void score_select_kernel(
     for (int base = 0; base < L; base += kSelThreads * kItems) {
         const int j0 = base + tid * kItems;
         uint32_t fgt = 0, feq = 0;  // bit masks over the thread's items
+        uint64_t kv[kItems];
+#pragma unroll
+        for (int i = 0; i < kItems; ++i) kv[i] = (j0 + i < L) ? keys[j0 + i] : 0ull;
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
             if (j0 + i < L) {
-                const uint64_t k = keys[j0 + i];
-                fgt |= (k > thr) ? (1u << i) : 0u;
-                feq |= (k == thr) ? (1u << i) : 0u;
+                fgt |= (kv[i] > thr) ? (1u << i) : 0u;
+                feq |= (kv[i] == thr) ? (1u << i) : 0u;
             }
         }
         const uint32_t cg = __popc(fgt), ce = __popc(feq);
@@ -331,7 +525,7 @@ __global__ __launch_bounds__(kThreads) void copy_back_kernel(
 }
 
 struct WsLayout {
-    size_t tokinfo, r, keys, psum, ssum, stage_k, stage_v, total;
+    size_t tokinfo, r, keys, psum, ssum, pmax, stage_k, stage_v, total;
     int nblk;
 };
 
@@ -349,6 +543,7 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     w.keys = off;    off += fc_align_up((size_t)H * L * 8);
     w.psum = off;    off += fc_align_up((size_t)H * nblk * d * 8);
     w.ssum = off;    off += fc_align_up((size_t)H * d * 8);
+    w.pmax = off;    off += fc_align_up((size_t)H * nblk * 8);
     const size_t b = (budget < L) ? (size_t)budget : 0;
     w.stage_k = off; off += fc_align_up((size_t)H * b * d * esz);
     w.stage_v = off; off += fc_align_up((size_t)H * b * d * esz);
@@ -365,6 +560,8 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s) {
     uint64_t* keys = reinterpret_cast<uint64_t*>(ws + w.keys);
     double* psum = reinterpret_cast<double*>(ws + w.psum);
     double* ssum = reinterpret_cast<double*>(ws + w.ssum);
+    double* pmax = reinterpret_cast<double*>(ws + w.pmax);
+    double* etmp = reinterpret_cast<double*>(tokinfo);   // token info is dead once r exists
     uint4* stage_k = reinterpret_cast<uint4*>(ws + w.stage_k);
     uint4* stage_v = reinterpret_cast<uint4*>(ws + w.stage_v);
     const T* kc = reinterpret_cast<const T*>(a.k_cache);
@@ -372,13 +569,13 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s) {
     key_stats_kernel<T, D><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
                                                                    a.L_k, tokinfo, psum);
     FC_LAUNCH_CHECK();
-    sum_partials_kernel<D><<<a.H_k, D, 0, s>>>(psum, w.nblk, ssum);
+    sum_partials_kernel<D><<<a.H_k, 1024, 0, s>>>(psum, w.nblk, ssum);
     FC_LAUNCH_CHECK();
     mean_sim_kernel<T, D><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
-                                                                  a.L_k, tokinfo, ssum, r);
+                                                                  a.L_k, tokinfo, ssum, r, pmax);
     FC_LAUNCH_CHECK();
-    score_select_kernel<<<a.H_k, kSelThreads, 0, s>>>(r, a.mass, a.L_k, a.budget, a.pool_k,
-                                                      a.lambda, keys, a.kept);
+    score_select_kernel<<<a.H_k, kSelThreads, 0, s>>>(r, a.mass, pmax, w.nblk, a.L_k, a.budget,
+                                                      a.pool_k, a.lambda, etmp, keys, a.kept);
     FC_LAUNCH_CHECK();
     const int vpr = D * (int)sizeof(T) / 16;
     const int64_t hs = a.head_stride * (int64_t)sizeof(T) / 16, ts = a.tok_stride * (int64_t)sizeof(T) / 16;
