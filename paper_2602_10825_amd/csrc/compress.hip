@@ -5,13 +5,23 @@
 //                  partial sum of normalised keys                      (HBM-bound)
 //   sum_partials   per head: fixed-order sum of the block partials -> s = sum_i k^_i
 //   mean_sim       pass 2 over K: r_j = (k^_j . s - k^_j . k^_j) / L   (HBM-bound), the
-//                  linear-time form of the diagonal-zeroed column mean of Eq. (11)
-//   score_select   per head: softmax over r (Eq. (11)), max-pooled importance (Eq. (10)),
-//                  score (Eq. (12)) -> order-preserving 64-bit keys; radix select of the
-//                  budget-th largest key, started at the most significant bit in which
-//                  the keys differ and finished on the few candidates left, in LDS; ordered
-//                  compaction of the kept positions (ties: lower position wins; ascending)
-//   gather_rows / copy_back   move kept K and V rows to positions [0, budget)
+//                  linear-time form of the diagonal-zeroed column mean of Eq. (11);
+//                  writes e_j = exp(r_j) and block partial sums of e.  (The softmax of
+//                  Eq. (11) is shift-invariant and |r_j| <= 1 + 1/L, so no max is
+//                  subtracted.)
+//   score_keys     Red_j = e_j / sum e (Eq. (11)), max-pooled importance (Eq. (10)), score
+//                  (Eq. (12)) -> order-preserving 64-bit keys, block min / max of the keys
+//   key_hist       histogram of the first 11 bits in which the keys of a head differ
+//   select         per head: radix select of the budget-th largest key, continued from
+//                  that histogram and finished on the few candidates left, in LDS
+//   write_kept     ordered compaction of the kept positions (ties: lower position wins;
+//                  output ascending); a block counts what precedes it by itself
+//   compact_rows   move the kept K and V rows to positions [0, budget) IN PLACE, one pass:
+//                  a block takes a ticket (tile-major, so a head's tiles start in order),
+//                  loads the 64 source rows of its tile into registers, publishes "tile
+//                  read", waits until every lower tile of the head has published (only those
+//                  can still need rows the block is about to overwrite, and they are already
+//                  running, so the wait ends), then stores.
 // A 16-lane group owns one token row in the two passes over K (16-byte loads, a full
 // row per group), so a token's values never depend on where it sits in the launch.
 #include "fc_common.hpp"
@@ -24,6 +34,11 @@ constexpr int kThreads = 256;
 constexpr int kGroups = kThreads / 16;
 constexpr int kSelThreads = 1024;
 constexpr int kItems = 8;
+constexpr int kTokBlk = kThreads * kItems;   // tokens per block in the per-token kernels
+constexpr int kDigitBits = 11;
+constexpr int kBins = 1 << kDigitBits;
+constexpr int kCand = 4096;   // candidates resolved in LDS
+constexpr int kUnroll = 8;    // independent loads in flight per thread in the selection scans
 
 // ---- per-lane slice of one token row, widened exactly to float64 ---------------------
 template <typename T, int D>
@@ -125,7 +140,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
     const double2* __restrict__ tokinfo, const double* __restrict__ ssum,
-    double* __restrict__ r, double* __restrict__ pmax) {
+    double* __restrict__ e_out, double* __restrict__ pz) {
     constexpr int EL = D / 16;
     const int h = blockIdx.y;
     const int g = threadIdx.x / 16, u = threadIdx.x % 16;
@@ -134,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
 #pragma unroll
     for (int e = 0; e < EL; ++e) s[e] = ssum[h * D + u * EL + e];
     const double dL = (double)L;
-    double rmax = -1.0e300;
+    double zsum = 0.0;
     for (int j = blockIdx.x * kGroups + g; j < L; j += gridDim.x * kGroups) {
         double x[EL];
         load_slice<T, D>(base + (int64_t)j * tok_stride, u, x);
@@ -144,58 +159,36 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
         dot = group_sum(dot);
         if (u == 0) {
             const double2 ti = tokinfo[(int64_t)h * L + j];
-            const double rj = (dot * ti.x - ti.y) / dL;
-            r[(int64_t)h * L + j] = rj;
-            rmax = fmax(rmax, rj);
+            const double ej = exp((dot * ti.x - ti.y) / dL);
+            e_out[(int64_t)h * L + j] = ej;
+            zsum += ej;
         }
     }
-    __shared__ double shm[kGroups];
-    if (u == 0) shm[g] = rmax;
+    __shared__ double shz[kGroups];
+    if (u == 0) shz[g] = zsum;
     __syncthreads();
     if (threadIdx.x == 0) {
-        double m = shm[0];
+        double z = 0.0;
 #pragma unroll
-        for (int k = 1; k < kGroups; ++k) m = fmax(m, shm[k]);
-        pmax[(int64_t)h * gridDim.x + blockIdx.x] = m;
+        for (int k = 0; k < kGroups; ++k) z += shz[k];
+        pz[(int64_t)h * gridDim.x + blockIdx.x] = z;
     }
 }
 
-// ---- block-wide helpers for the per-head selection kernel (1024 threads) --------------
-__device__ __forceinline__ double block_max_d(double v, double* sh) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, FC_WAVE));
-    const int w = threadIdx.x / FC_WAVE;
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) sh[w] = v;
-    __syncthreads();
-    double m = sh[0];
-    for (int k = 1; k < kSelThreads / FC_WAVE; ++k) m = fmax(m, sh[k]);
-    return m;
-}
-
-// fixed-shape tree: deterministic for a given block size
-__device__ __forceinline__ double block_sum_d(double v, double* sh) {
+// fixed-shape tree over the block: deterministic, and identical in every block that runs it
+template <int NT>
+__device__ __forceinline__ double block_sum_fixed(double v, double* sh) {
     __syncthreads();
     sh[threadIdx.x] = v;
     __syncthreads();
-    for (int s = kSelThreads / 2; s > 0; s >>= 1) {
-        if (threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+    for (int s = NT / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
         __syncthreads();
     }
     return sh[0];
 }
 
-__device__ __forceinline__ uint64_t score_key(double score) {
-    if (score == 0.0) score = 0.0;  // -0 -> +0
-    const uint64_t b = (uint64_t)__double_as_longlong(score);
-    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
-}
-
-constexpr int kDigitBits = 11;
-constexpr int kBins = 1 << kDigitBits;
-constexpr int kCand = 4096;   // candidates resolved in LDS
-constexpr int kUnroll = 8;    // independent loads in flight per thread in the selection scans
-
+template <int NT>
 __device__ __forceinline__ uint64_t block_reduce_u64(uint64_t v, bool want_max, uint64_t* sh) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -206,8 +199,96 @@ __device__ __forceinline__ uint64_t block_reduce_u64(uint64_t v, bool want_max, 
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x / FC_WAVE] = v;
     __syncthreads();
     uint64_t m = sh[0];
-    for (int k = 1; k < kSelThreads / FC_WAVE; ++k) m = want_max ? (sh[k] > m ? sh[k] : m) : (sh[k] < m ? sh[k] : m);
+    for (int k = 1; k < NT / FC_WAVE; ++k) m = want_max ? (sh[k] > m ? sh[k] : m) : (sh[k] < m ? sh[k] : m);
     return m;
+}
+
+__device__ __forceinline__ uint64_t score_key(double score) {
+    if (score == 0.0) score = 0.0;  // -0 -> +0
+    const uint64_t b = (uint64_t)__double_as_longlong(score);
+    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+
+
+// ---- keys: Eq. (10)-(12) per token, fully parallel ------------------------------------
+__global__ __launch_bounds__(kThreads) void score_keys_kernel(
+    const double* __restrict__ e_all, const float* __restrict__ mass_all,
+    const double* __restrict__ pz_all, int nblkz, int L, int pool_k, double lambda,
+    uint64_t* __restrict__ keys_all, uint64_t* __restrict__ pminmax, uint32_t* __restrict__ hist_all,
+    uint32_t* __restrict__ sync, int ntile) {
+    const int h = blockIdx.y, tid = threadIdx.x;
+    const double* e = e_all + (int64_t)h * L;
+    const float* mass = mass_all + (int64_t)h * L;
+    uint64_t* keys = keys_all + (int64_t)h * L;
+    __shared__ double shd[kThreads];
+    __shared__ uint64_t shu[kThreads / FC_WAVE];
+    if (blockIdx.x == 0) {   // state later kernels of this call start from: histogram, tile flags
+        for (int i = tid; i < kBins; i += kThreads) hist_all[(int64_t)h * kBins + i] = 0u;
+        for (int i = tid; i < ntile; i += kThreads) sync[64 * (gridDim.y + 1) + (int64_t)h * ntile + i] = 0u;
+        if (tid == 0) sync[64 * (h + 1)] = 0u;
+        if (h == 0 && tid == 0) sync[0] = 0u;
+    }
+    // Z = sum_j e_j: the block partials of the pass that wrote e, in a fixed order
+    double z = 0.0;
+    for (int i = tid; i < nblkz; i += kThreads) z += pz_all[(int64_t)h * nblkz + i];
+    z = block_sum_fixed<kThreads>(z, shd);
+
+    const int half = pool_k / 2;
+    const int j0 = blockIdx.x * kTokBlk;
+    double ev[kItems];
+    float imp[kItems];
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int j = j0 + i * kThreads + tid;
+        ev[i] = (j < L) ? e[j] : 0.0;
+        imp[i] = (j < L) ? mass[j] : 0.f;
+    }
+    for (int d = 1; d <= half; ++d) {   // Eq. (10): window max, -inf outside [0, L)
+#pragma unroll
+        for (int i = 0; i < kItems; ++i) {
+            const int j = j0 + i * kThreads + tid;
+            if (j < L) {
+                const float lo = (j - d >= 0) ? mass[j - d] : imp[i];
+                const float hi = (j + d < L) ? mass[j + d] : imp[i];
+                imp[i] = fmaxf(imp[i], fmaxf(lo, hi));
+            }
+        }
+    }
+    uint64_t kmin = ~0ull, kmax = 0ull;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int j = j0 + i * kThreads + tid;
+        if (j < L) {
+            const double red = ev[i] / z;                    // Eq. (11)
+            const double a = lambda * (double)imp[i];
+            const double b = (1.0 - lambda) * red;
+            const uint64_t k = score_key(a - b);             // Eq. (12)
+            keys[j] = k;
+            kmin = k < kmin ? k : kmin;
+            kmax = k > kmax ? k : kmax;
+        }
+    }
+    kmin = block_reduce_u64<kThreads>(kmin, false, shu);
+    kmax = block_reduce_u64<kThreads>(kmax, true, shu);
+    if (tid == 0) {
+        pminmax[((int64_t)h * gridDim.x + blockIdx.x) * 2] = kmin;
+        pminmax[((int64_t)h * gridDim.x + blockIdx.x) * 2 + 1] = kmax;
+    }
+}
+
+// min and max key of a head from the block partials (every caller gets the same values)
+template <int NT>
+__device__ __forceinline__ void head_minmax(const uint64_t* __restrict__ pminmax, int h, int nb,
+                                            uint64_t* sh, uint64_t& kmin, uint64_t& kmax) {
+    uint64_t lo = ~0ull, hi = 0ull;
+    for (int i = threadIdx.x; i < nb; i += NT) {
+        const uint64_t a = pminmax[((int64_t)h * nb + i) * 2], b = pminmax[((int64_t)h * nb + i) * 2 + 1];
+        lo = a < lo ? a : lo;
+        hi = b > hi ? b : hi;
+    }
+    kmin = block_reduce_u64<NT>(lo, false, sh);
+    kmax = block_reduce_u64<NT>(hi, true, sh);
+    __syncthreads();
 }
 
 // From a histogram of `nb` <= 2048 bins (counts of the current candidates by digit), find the
@@ -274,136 +355,101 @@ __device__ __forceinline__ void list_append(uint64_t* list, uint32_t* counter, b
     if (take) list[base + __popcll(m & ((1ull << lane) - 1ull))] = k;
 }
 
-__global__ __launch_bounds__(kSelThreads) void score_select_kernel(
-    const double* __restrict__ r_all, const float* __restrict__ mass_all,
-    const double* __restrict__ pmax_all, int nblk, int L, int budget, int pool_k, double lambda,
-    double* __restrict__ etmp_all, uint64_t* __restrict__ keys_all, int32_t* __restrict__ kept_all) {
+// ---- first radix pass, parallel: all keys of a head agree above bit `top`; count the
+//      next kDigitBits bits
+__global__ __launch_bounds__(kThreads) void key_hist_kernel(const uint64_t* __restrict__ keys_all,
+                                                            const uint64_t* __restrict__ pminmax,
+                                                            int L, uint32_t* __restrict__ hist_all) {
+    const int h = blockIdx.y, tid = threadIdx.x;
+    const uint64_t* keys = keys_all + (int64_t)h * L;
+    __shared__ uint64_t shu[kThreads / FC_WAVE];
+    __shared__ uint32_t hist[kBins];
+    uint64_t kmin, kmax;
+    head_minmax<kThreads>(pminmax, h, gridDim.x, shu, kmin, kmax);
+    const uint64_t diff = kmin ^ kmax;
+    if (diff == 0) return;   // all scores equal: nothing to count
+    const int rem = 64 - __clzll((long long)diff);
+    const int w = rem < kDigitBits ? rem : kDigitBits;
+    const int shift = rem - w;
+    for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
+    __syncthreads();
+    const int j0 = blockIdx.x * kTokBlk;
+    uint64_t kv[kItems];
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int j = j0 + i * kThreads + tid;
+        kv[i] = (j < L) ? keys[j] : 0ull;
+    }
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+        hist_add(hist, j0 + i * kThreads + tid < L, (uint32_t)(kv[i] >> shift) & ((1u << w) - 1u));
+    __syncthreads();
+    for (int i = tid; i < kBins; i += kThreads)
+        if (hist[i]) atomicAdd(&hist_all[(int64_t)h * kBins + i], hist[i]);
+}
+
+// ---- per head: finish the radix select -> threshold key and the number of its copies kept
+__global__ __launch_bounds__(kSelThreads) void select_kernel(
+    const uint64_t* __restrict__ keys_all, const uint64_t* __restrict__ pminmax, int nb2,
+    const uint32_t* __restrict__ hist_all, int L, int budget, uint64_t* __restrict__ sel) {
     const int h = blockIdx.x;
     const int tid = threadIdx.x;
-    const double* r = r_all + (int64_t)h * L;
-    const float* mass = mass_all + (int64_t)h * L;
-    double* etmp = etmp_all + (int64_t)h * L;
-    uint64_t* keys = keys_all + (int64_t)h * L;
-    int32_t* kept = kept_all + (int64_t)h * budget;
-
-    __shared__ double shd[kSelThreads];
+    const uint64_t* keys = keys_all + (int64_t)h * L;
     __shared__ uint64_t shu[kSelThreads / FC_WAVE];
     __shared__ uint32_t hist[kBins];
     __shared__ uint64_t cand[kCand];
-    __shared__ uint32_t wtot[2][kSelThreads / FC_WAVE];
+    __shared__ uint32_t wtot[kSelThreads / FC_WAVE];
     __shared__ uint64_t sh_prefix;
     __shared__ uint32_t sh_need, sh_count, sh_ncand;
 
-    // Eq. (11): softmax over the token index of r.  max r comes from the block maxima of
-    // the pass that produced r.
-    double mx = -1.0e300;
-    for (int i = tid; i < nblk; i += kSelThreads) mx = fmax(mx, pmax_all[(int64_t)h * nblk + i]);
-    mx = block_max_d(mx, shd);
-    // All scans below fetch kUnroll independent elements per thread before using them: one
-    // block per head is latency-bound otherwise.
-    double z = 0.0;
-    for (int base = 0; base < L; base += kSelThreads * kUnroll) {
-        double rv[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * kSelThreads + tid;
-            rv[u] = (j < L) ? r[j] : 0.0;
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * kSelThreads + tid;
-            if (j < L) {
-                const double e = exp(rv[u] - mx);
-                etmp[j] = e;
-                z += e;
-            }
-        }
-    }
-    z = block_sum_d(z, shd);
-
-    // Eq. (10) + Eq. (12) -> sortable keys; their min and max bound the bits that matter
-    const int half = pool_k / 2;
-    uint64_t kmin = ~0ull, kmax = 0ull;
-    for (int base = 0; base < L; base += kSelThreads * kUnroll) {
-        double ev[kUnroll];
-        float imp[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * kSelThreads + tid;
-            ev[u] = (j < L) ? etmp[j] : 0.0;
-            imp[u] = (j < L) ? mass[j] : 0.f;
-        }
-        for (int d = 1; d <= half; ++d) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int j = base + u * kSelThreads + tid;
-                if (j < L) {
-                    const float lo = (j - d >= 0) ? mass[j - d] : imp[u];
-                    const float hi = (j + d < L) ? mass[j + d] : imp[u];
-                    imp[u] = fmaxf(imp[u], fmaxf(lo, hi));
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * kSelThreads + tid;
-            if (j < L) {
-                const double red = ev[u] / z;
-                const double a = lambda * (double)imp[u];
-                const double b = (1.0 - lambda) * red;
-                const uint64_t k = score_key(a - b);
-                keys[j] = k;
-                kmin = k < kmin ? k : kmin;
-                kmax = k > kmax ? k : kmax;
-            }
-        }
-    }
-    kmin = block_reduce_u64(kmin, false, shu);
-    kmax = block_reduce_u64(kmax, true, shu);
-    __syncthreads();
-
-    // Radix select of the budget-th largest key.  All keys agree above bit `top`.
+    uint64_t kmin, kmax;
+    head_minmax<kSelThreads>(pminmax, h, nb2, shu, kmin, kmax);
     uint64_t thr;
     uint32_t need = (uint32_t)budget;
     const uint64_t diff = kmin ^ kmax;
     if (diff == 0) {
         thr = kmax;   // every score is the same: keep the first `budget` positions
     } else {
-        const int top = 63 - __clzll((long long)diff);
-        int rem = top + 1;                                         // undecided low bits
+        int rem = 64 - __clzll((long long)diff);                   // undecided low bits
         uint64_t prefix = (rem == 64) ? 0ull : (kmax >> rem) << rem;
-        bool in_lds = false;
+        bool in_lds = false, first = true;
         uint32_t ncand = 0;
         while (rem > 0) {
             const int w = in_lds ? (rem < 8 ? rem : 8) : (rem < kDigitBits ? rem : kDigitBits);
             const int shift = rem - w;
             const int nb = 1 << w;
-            for (int i = tid; i < nb; i += kSelThreads) hist[i] = 0;
-            __syncthreads();
             const uint64_t himask = (rem == 64) ? 0ull : (~0ull << rem);
-            if (in_lds) {
-                for (uint32_t i0 = 0; i0 < ncand; i0 += kSelThreads) {
-                    const uint32_t i = i0 + tid;
-                    const uint64_t k = (i < ncand) ? cand[i] : ~prefix;
-                    hist_add(hist, i < ncand && (k & himask) == prefix, (uint32_t)(k >> shift) & (nb - 1));
-                }
+            if (first) {   // counted by key_hist_kernel
+                for (int i = tid; i < nb; i += kSelThreads) hist[i] = hist_all[(int64_t)h * kBins + i];
             } else {
-                for (int base = 0; base < L; base += kSelThreads * kUnroll) {
-                    uint64_t kv[kUnroll];
-#pragma unroll
-                    for (int u = 0; u < kUnroll; ++u) {
-                        const int j = base + u * kSelThreads + tid;
-                        kv[u] = (j < L) ? keys[j] : ~prefix;   // padding never matches the prefix
+                for (int i = tid; i < nb; i += kSelThreads) hist[i] = 0;
+                __syncthreads();
+                if (in_lds) {
+                    for (uint32_t i0 = 0; i0 < ncand; i0 += kSelThreads) {
+                        const uint32_t i = i0 + tid;
+                        const uint64_t k = (i < ncand) ? cand[i] : 0ull;
+                        hist_add(hist, i < ncand && (k & himask) == prefix,
+                                 (uint32_t)(k >> shift) & (nb - 1));
                     }
+                } else {
+                    for (int base = 0; base < L; base += kSelThreads * kUnroll) {
+                        uint64_t kv[kUnroll];
 #pragma unroll
-                    for (int u = 0; u < kUnroll; ++u)
-                        hist_add(hist, (kv[u] & himask) == prefix && base + u * kSelThreads + tid < L,
-                                 (uint32_t)(kv[u] >> shift) & (nb - 1));
+                        for (int u = 0; u < kUnroll; ++u) {
+                            const int j = base + u * kSelThreads + tid;
+                            kv[u] = (j < L) ? keys[j] : 0ull;
+                        }
+#pragma unroll
+                        for (int u = 0; u < kUnroll; ++u)
+                            hist_add(hist, (kv[u] & himask) == prefix && base + u * kSelThreads + tid < L,
+                                     (uint32_t)(kv[u] >> shift) & (nb - 1));
+                    }
                 }
             }
+            first = false;
             __syncthreads();
             if (tid == 0) sh_ncand = 0;
-            pick_bin_parallel(hist, nb, need, wtot[0], prefix, shift, &sh_prefix, &sh_need, &sh_count);
+            pick_bin_parallel(hist, nb, need, wtot, prefix, shift, &sh_prefix, &sh_need, &sh_count);
             __syncthreads();
             prefix = sh_prefix;
             need = sh_need;
@@ -430,55 +476,76 @@ __global__ __launch_bounds__(kSelThreads) void score_select_kernel(
         }
         thr = prefix;
     }
+    if (tid == 0) {
+        sel[2 * h] = thr;
+        sel[2 * h + 1] = need;
+    }
+}
 
-    // ordered compaction: position = #greater before + min(#equal before, need)
-    uint32_t run_gt = 0, run_eq = 0;
+// ---- ordered compaction of the kept positions: position = #greater before + min(#equal
+//      before, need).  A block first counts the tokens that precede its own 2048.
+__global__ __launch_bounds__(kThreads) void write_kept_kernel(const uint64_t* __restrict__ keys_all,
+                                                              const uint64_t* __restrict__ sel, int L,
+                                                              int budget, int32_t* __restrict__ kept_all) {
+    const int h = blockIdx.y, tid = threadIdx.x;
     const int wave = tid / FC_WAVE, lane = tid & 63;
-    for (int base = 0; base < L; base += kSelThreads * kItems) {
-        const int j0 = base + tid * kItems;
-        uint32_t fgt = 0, feq = 0;  // bit masks over the thread's items
-        uint64_t kv[kItems];
+    const uint64_t* keys = keys_all + (int64_t)h * L;
+    int32_t* kept = kept_all + (int64_t)h * budget;
+    const uint64_t thr = sel[2 * h];
+    const uint32_t need = (uint32_t)sel[2 * h + 1];
+    __shared__ uint32_t wtot[2][kThreads / FC_WAVE];
+    const int first = blockIdx.x * kTokBlk;
+
+    uint32_t ng = 0, ne = 0;
+    for (int base = 0; base < first; base += kThreads * kUnroll) {
+        uint64_t kv[kUnroll];
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) kv[i] = (j0 + i < L) ? keys[j0 + i] : 0ull;
+        for (int u = 0; u < kUnroll; ++u) kv[u] = keys[base + u * kThreads + tid];   // first % 2048 == 0
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) {
-            if (j0 + i < L) {
-                fgt |= (kv[i] > thr) ? (1u << i) : 0u;
-                feq |= (kv[i] == thr) ? (1u << i) : 0u;
-            }
-        }
-        const uint32_t cg = __popc(fgt), ce = __popc(feq);
-        // inclusive wave scans
-        uint32_t sg = cg, se = ce;
+        for (int u = 0; u < kUnroll; ++u) { ng += kv[u] > thr; ne += kv[u] == thr; }
+    }
 #pragma unroll
-        for (int o = 1; o < FC_WAVE; o <<= 1) {
-            const uint32_t tg = __shfl_up(sg, o, FC_WAVE);
-            const uint32_t te = __shfl_up(se, o, FC_WAVE);
-            if (lane >= o) { sg += tg; se += te; }
-        }
-        __syncthreads();
-        if (lane == 63) { wtot[0][wave] = sg; wtot[1][wave] = se; }
-        __syncthreads();
-        uint32_t pg = run_gt, pe = run_eq, allg = 0, alle = 0;
-        for (int w = 0; w < kSelThreads / FC_WAVE; ++w) {
-            if (w < wave) { pg += wtot[0][w]; pe += wtot[1][w]; }
-            allg += wtot[0][w];
-            alle += wtot[1][w];
-        }
-        uint32_t gt_before = pg + sg - cg;
-        uint32_t eq_before = pe + se - ce;
+    for (int o = 32; o > 0; o >>= 1) { ng += __shfl_xor(ng, o, FC_WAVE); ne += __shfl_xor(ne, o, FC_WAVE); }
+    if (lane == 0) { wtot[0][wave] = ng; wtot[1][wave] = ne; }
+    __syncthreads();
+    uint32_t base_gt = 0, base_eq = 0;
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) {
-            const bool g = (fgt >> i) & 1u, e = (feq >> i) & 1u;
-            if (g || (e && eq_before < need)) {
-                const uint32_t pos = gt_before + (eq_before < need ? eq_before : need);
-                kept[pos] = j0 + i;
-            }
-            gt_before += g ? 1u : 0u;
-            eq_before += e ? 1u : 0u;
+    for (int w = 0; w < kThreads / FC_WAVE; ++w) { base_gt += wtot[0][w]; base_eq += wtot[1][w]; }
+    __syncthreads();
+
+    const int j0 = first + tid * kItems;   // contiguous items per thread: order = position
+    uint32_t fgt = 0, feq = 0;
+    uint64_t kv[kItems];
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) kv[i] = (j0 + i < L) ? keys[j0 + i] : 0ull;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        if (j0 + i < L) {
+            fgt |= (kv[i] > thr) ? (1u << i) : 0u;
+            feq |= (kv[i] == thr) ? (1u << i) : 0u;
         }
-        run_gt += allg;
-        run_eq += alle;
+    }
+    const uint32_t cg = __popc(fgt), ce = __popc(feq);
+    uint32_t sg = cg, se = ce;   // inclusive wave scans
+#pragma unroll
+    for (int o = 1; o < FC_WAVE; o <<= 1) {
+        const uint32_t tg = __shfl_up(sg, o, FC_WAVE);
+        const uint32_t te = __shfl_up(se, o, FC_WAVE);
+        if (lane >= o) { sg += tg; se += te; }
+    }
+    if (lane == 63) { wtot[0][wave] = sg; wtot[1][wave] = se; }
+    __syncthreads();
+    uint32_t gt_before = base_gt + sg - cg, eq_before = base_eq + se - ce;
+    for (int w = 0; w < wave; ++w) { gt_before += wtot[0][w]; eq_before += wtot[1][w]; }
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const bool g = (fgt >> i) & 1u, e = (feq >> i) & 1u;
+        if (g || (e && eq_before < need)) {
+            const uint32_t pos = gt_before + (eq_before < need ? eq_before : need);
+            kept[pos] = j0 + i;
+        }
+        gt_before += g ? 1u : 0u;
+        eq_before += e ? 1u : 0u;
     }
 }
 
@@ -487,46 +554,79 @@ __global__ void iota_kernel(int32_t* kept, int H, int n) {
     if (i < (int64_t)H * n) kept[i] = (int32_t)(i % n);
 }
 
-// ---- compaction: kept rows -> staging -> positions [0, budget) ------------------------
-// rows are `vpr` 16-byte vectors; a row whose position does not change is skipped.
-__global__ __launch_bounds__(kThreads) void gather_rows_kernel(
-    const uint4* __restrict__ k_cache, const uint4* __restrict__ v_cache, int64_t head_stride_v,
-    int64_t tok_stride_v, int vpr, int budget, const int32_t* __restrict__ kept,
-    uint4* __restrict__ stage_k, uint4* __restrict__ stage_v) {
-    const int h = blockIdx.y;
-    const int64_t total = (int64_t)budget * vpr;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
-        const int s = (int)(i / vpr), v = (int)(i % vpr);
-        const int src = kept[(int64_t)h * budget + s];
-        if (src == s) continue;
-        const int64_t a = h * head_stride_v + (int64_t)src * tok_stride_v + v;
-        const int64_t d = ((int64_t)h * budget + s) * vpr + v;
-        stage_k[d] = k_cache[a];
-        stage_v[d] = v_cache[a];
-    }
-}
+// ---- in-place compaction ---------------------------------------------------------------
+constexpr int kTileRows = 64;
+constexpr uint32_t kSpinLimit = 1u << 24;
 
-__global__ __launch_bounds__(kThreads) void copy_back_kernel(
+// rows are VPR 16-byte vectors.  sync[0] = error word, sync[64 * (h + 1)] = ticket counter of
+// head h (one per 256-byte line: same-line atomics serialise), sync[64 * (H + 1) + h * ntile + t]
+// = "tile t of head h has been read" -- all zeroed earlier in the call.  grid = (ntile, H).
+template <int VPR>
+__global__ __launch_bounds__(kThreads) void compact_rows_kernel(
     uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, int64_t head_stride_v,
-    int64_t tok_stride_v, int vpr, int budget, const int32_t* __restrict__ kept,
-    const uint4* __restrict__ stage_k, const uint4* __restrict__ stage_v) {
+    int64_t tok_stride_v, int H, int L, int budget, int ntile, const int32_t* __restrict__ kept_all,
+    uint32_t* __restrict__ sync) {
+    constexpr int LDN = kTileRows * VPR / kThreads;   // vectors per thread per matrix
+    constexpr int RPP = kThreads / VPR;               // rows per pass
+    __shared__ int sh_tile;
+    const int tid = threadIdx.x;
     const int h = blockIdx.y;
-    const int64_t total = (int64_t)budget * vpr;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
-        const int s = (int)(i / vpr), v = (int)(i % vpr);
-        if (kept[(int64_t)h * budget + s] == s) continue;
-        const int64_t a = h * head_stride_v + (int64_t)s * tok_stride_v + v;
-        const int64_t d = ((int64_t)h * budget + s) * vpr + v;
-        k_cache[a] = stage_k[d];
-        v_cache[a] = stage_v[d];
+    const int32_t* kept = kept_all + (int64_t)h * budget;
+    uint32_t* flags = sync + 64 * (H + 1) + (int64_t)h * ntile;
+    if (tid == 0) sh_tile = (int)atomicAdd(&sync[64 * (h + 1)], 1u);   // a head's tiles start in order
+    __syncthreads();
+    const int tile = sh_tile;
+    const int row0 = tile * kTileRows;
+    const int lrow = tid / VPR, lcol = tid % VPR;
+
+    uint4 kr[LDN], vr[LDN];
+    int src[LDN];
+#pragma unroll
+    for (int p = 0; p < LDN; ++p) {
+        const int s = row0 + p * RPP + lrow;
+        src[p] = (s < budget) ? kept[s] : -1;
+        if (src[p] >= L) src[p] = -1;   // never read outside the compressed range
+        if (src[p] >= 0 && src[p] != s) {
+            const int64_t a = h * head_stride_v + (int64_t)src[p] * tok_stride_v + lcol;
+            kr[p] = k_cache[a];
+            vr[p] = v_cache[a];
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the rows are in registers
+    __syncthreads();
+    // No fence: nothing this block wrote has to become visible -- only the ORDER "rows loaded,
+    // then flag" matters, and the loads have returned.  (A release fence here would write back
+    // the whole L2 of this XCD, once per block.)
+    if (tid == 0) __hip_atomic_fetch_or(&flags[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // Wait for the lower tiles that read from this tile's rows: tile t does iff its last (=
+    // largest) source row is >= row0.  They hold lower tickets, so they are already running,
+    // and they publish before they wait: the wait ends.
+    bool ok = true;
+    for (int t = tid; t < tile; t += kThreads) {
+        const int last = ((t + 1) * kTileRows < budget ? (t + 1) * kTileRows : budget) - 1;
+        if (kept[last] < row0) continue;
+        uint32_t spins = 0;
+        while (__hip_atomic_load(&flags[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+            if (++spins > kSpinLimit) { ok = false; break; }
+            __builtin_amdgcn_s_sleep(2);
+        }
+    }
+    if (!ok) atomicOr(&sync[0], 1u);
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < LDN; ++p) {
+        const int s = row0 + p * RPP + lrow;
+        if (src[p] >= 0 && src[p] != s) {
+            const int64_t a = h * head_stride_v + (int64_t)s * tok_stride_v + lcol;
+            k_cache[a] = kr[p];
+            v_cache[a] = vr[p];
+        }
     }
 }
 
 struct WsLayout {
-    size_t tokinfo, r, keys, psum, ssum, pmax, stage_k, stage_v, total;
-    int nblk;
+    size_t tokinfo, e, keys, psum, ssum, pz, pminmax, hist, sel, sync, total;
+    int nblk, nb2, ntile;
 };
 
 WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
@@ -536,17 +636,21 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     if (nblk > cap) nblk = cap;
     if (nblk < 1) nblk = 1;
     w.nblk = nblk;
+    w.nb2 = (L + kTokBlk - 1) / kTokBlk;
     const size_t esz = (dtype == FC_BF16) ? 2 : 4;
     size_t off = 0;
     w.tokinfo = off; off += fc_align_up((size_t)H * L * 16);
-    w.r = off;       off += fc_align_up((size_t)H * L * 8);
+    w.e = off;       off += fc_align_up((size_t)H * L * 8);
     w.keys = off;    off += fc_align_up((size_t)H * L * 8);
     w.psum = off;    off += fc_align_up((size_t)H * nblk * d * 8);
     w.ssum = off;    off += fc_align_up((size_t)H * d * 8);
-    w.pmax = off;    off += fc_align_up((size_t)H * nblk * 8);
-    const size_t b = (budget < L) ? (size_t)budget : 0;
-    w.stage_k = off; off += fc_align_up((size_t)H * b * d * esz);
-    w.stage_v = off; off += fc_align_up((size_t)H * b * d * esz);
+    w.pz = off;      off += fc_align_up((size_t)H * nblk * 8);
+    w.pminmax = off; off += fc_align_up((size_t)H * w.nb2 * 16);
+    w.hist = off;    off += fc_align_up((size_t)H * kBins * 4);
+    w.sel = off;     off += fc_align_up((size_t)H * 16);
+    w.ntile = (((budget < L) ? budget : L) + kTileRows - 1) / kTileRows;
+    w.sync = off;    off += fc_align_up(((size_t)H * w.ntile + 64 * ((size_t)H + 1)) * 4);
+    (void)esz;
     w.total = off;
     return w;
 }
@@ -556,14 +660,15 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s) {
     const WsLayout w = layout(a.H_k, a.L_k, a.d, a.budget, a.dtype);
     char* ws = reinterpret_cast<char*>(a.ws);
     double2* tokinfo = reinterpret_cast<double2*>(ws + w.tokinfo);
-    double* r = reinterpret_cast<double*>(ws + w.r);
+    double* e = reinterpret_cast<double*>(ws + w.e);
     uint64_t* keys = reinterpret_cast<uint64_t*>(ws + w.keys);
     double* psum = reinterpret_cast<double*>(ws + w.psum);
     double* ssum = reinterpret_cast<double*>(ws + w.ssum);
-    double* pmax = reinterpret_cast<double*>(ws + w.pmax);
-    double* etmp = reinterpret_cast<double*>(tokinfo);   // token info is dead once r exists
-    uint4* stage_k = reinterpret_cast<uint4*>(ws + w.stage_k);
-    uint4* stage_v = reinterpret_cast<uint4*>(ws + w.stage_v);
+    double* pz = reinterpret_cast<double*>(ws + w.pz);
+    uint64_t* pminmax = reinterpret_cast<uint64_t*>(ws + w.pminmax);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(ws + w.hist);
+    uint64_t* sel = reinterpret_cast<uint64_t*>(ws + w.sel);
+    uint32_t* sync = reinterpret_cast<uint32_t*>(ws + w.sync);
     const T* kc = reinterpret_cast<const T*>(a.k_cache);
 
     key_stats_kernel<T, D><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
@@ -572,20 +677,21 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s) {
     sum_partials_kernel<D><<<a.H_k, 1024, 0, s>>>(psum, w.nblk, ssum);
     FC_LAUNCH_CHECK();
     mean_sim_kernel<T, D><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
-                                                                  a.L_k, tokinfo, ssum, r, pmax);
+                                                                  a.L_k, tokinfo, ssum, e, pz);
     FC_LAUNCH_CHECK();
-    score_select_kernel<<<a.H_k, kSelThreads, 0, s>>>(r, a.mass, pmax, w.nblk, a.L_k, a.budget,
-                                                      a.pool_k, a.lambda, etmp, keys, a.kept);
+    score_keys_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(e, a.mass, pz, w.nblk, a.L_k, a.pool_k,
+                                                              a.lambda, keys, pminmax, hist, sync, w.ntile);
     FC_LAUNCH_CHECK();
-    const int vpr = D * (int)sizeof(T) / 16;
+    key_hist_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, pminmax, a.L_k, hist);
+    FC_LAUNCH_CHECK();
+    select_kernel<<<a.H_k, kSelThreads, 0, s>>>(keys, pminmax, w.nb2, hist, a.L_k, a.budget, sel);
+    FC_LAUNCH_CHECK();
+    write_kept_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, sel, a.L_k, a.budget, a.kept);
+    FC_LAUNCH_CHECK();
+    constexpr int VPR = D * (int)sizeof(T) / 16;
     const int64_t hs = a.head_stride * (int64_t)sizeof(T) / 16, ts = a.tok_stride * (int64_t)sizeof(T) / 16;
-    int gx = (int)(((int64_t)a.budget * vpr + kThreads * 4 - 1) / (kThreads * 4));
-    gx = gx < 1 ? 1 : (gx > 4096 ? 4096 : gx);
-    gather_rows_kernel<<<dim3(gx, a.H_k), kThreads, 0, s>>>(
-        (const uint4*)a.k_cache, (const uint4*)a.v_cache, hs, ts, vpr, a.budget, a.kept, stage_k, stage_v);
-    FC_LAUNCH_CHECK();
-    copy_back_kernel<<<dim3(gx, a.H_k), kThreads, 0, s>>>((uint4*)a.k_cache, (uint4*)a.v_cache, hs, ts,
-                                                          vpr, a.budget, a.kept, stage_k, stage_v);
+    compact_rows_kernel<VPR><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
+        (uint4*)a.k_cache, (uint4*)a.v_cache, hs, ts, a.H_k, a.L_k, a.budget, w.ntile, a.kept, sync);
     FC_LAUNCH_CHECK();
     return FC_OK;
 }
