@@ -31,13 +31,17 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak
+# HBM bytes per launch of the attention kernel on C2, from two rocprofv3 --pmc runs of this
+# script (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors calibrated on the 188 MB copy kernel
+# of the same runs; profiles/bench_C2_hbm_traffic.md)
+ATTEND_TRAFFIC_BYTES = {"C2-skyreels-v2-1.3B-like-bf16": int((913104.0 * 2.0 + 92596.9 * 1.0) * 1024)}
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2", choices=["C2", "C3", "mid"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
     ap.add_argument("--cpu-rows", type=int, default=256, help="oracle attention rows per chunk")
@@ -208,7 +212,10 @@ def main():
                    "lambda": wl.lam},
         "roofline": {"kernel": "attend_bf16_kernel", "bound": "mfma", "achieved": att_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": att_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None, "algorithmic_flops": flops, "ms": stage_ms["attend"]},
+                     "traffic": ATTEND_TRAFFIC_BYTES.get(wl.name), "algorithmic_flops": flops,
+                     "ms": stage_ms["attend"],
+                     "note": "a loop of nothing but bf16 MFMAs on random operands sustains 1330-1410 "
+                             "TFLOP/s on this chip (power-limited; profiles/peaks_measured.md)"},
         "kv_compress_GBps": cmp_bytes / (stage_ms["compress"] * 1e-3) / 1e9,
         "calls": [hbm("decide", dec_bytes), hbm("scatter", sc_bytes), hbm("mass", mass_bytes),
                   hbm("compress", cmp_bytes)],

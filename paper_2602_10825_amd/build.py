@@ -39,8 +39,14 @@ def build(verbose: bool = True) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}\n{res.stderr}")
+    # stand-alone probe of the achievable MFMA / HBM peaks (not part of the library)
+    probe = os.path.join(HERE, "peak_probe")
+    cmd = [HIPCC, *FLAGS, os.path.join(CSRC, "peak_probe.hip"), "-o", probe]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed on peak_probe.hip:\n{res.stdout}\n{res.stderr}")
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {probe}")
     return LIB
 
 
