@@ -4,10 +4,14 @@
 //   mass[h_k, j] = 1/(W*G) * sum over rows w and the G query heads of key head h_k of
 //                  softmax_j(q_w . k_j * scale), the softmax running over j < mass_len only.
 //
-// Two passes over the keys, both with one thread per key holding its key in registers:
-//   mass_stats  per-row running (max, sum-exp) per wavefront            -> partials
-//   mass_lse    per-row merge of the partials (fixed order)             -> log2-sum-exp
-//   mass_cols   per key: sum over rows of exp2(s - lse), fixed order    -> mass
+// Two passes over the keys (the softmax normaliser of a row is known only after all keys):
+//   stats  per-row running (max, sum-exp) per block of keys             -> partials
+//   cols   per key: sum over rows of exp2(s - lse), fixed order         -> mass
+// bf16: both passes form S = Q K^T with v_mfma_f32_32x32x16_bf16 on 128-key tiles staged
+// through LDS by coalesced 16-byte loads (the passes are bound by the two reads of K);
+// the accumulator layout puts one key per lane and the 64 (padded) rows in registers, so
+// the per-key sum over rows is in-lane and the per-row statistics are kept per lane and
+// merged once per block.  fp32: one thread per key with its key in registers, fp32 FMA.
 // Rows are processed in groups of at most 64; groups accumulate into mass in launch
 // order, so the result is deterministic.  No atomics.
 #include "fc_common.hpp"
@@ -152,6 +156,257 @@ __global__ __launch_bounds__(kKeys) void mass_cols_kernel(FcMassArgs a, int w0, 
     }
 }
 
+
+// ---- bf16: matrix-core passes -------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kTile = 128;            // keys per tile: 4 wavefronts x 32 keys
+constexpr int kTilesPerBlock = 8;
+constexpr int kSpan = kTile * kTilesPerBlock;
+constexpr int kNT = 256;
+constexpr float kPosBig = 1.0e30f;
+
+template <int D>
+struct MassSmem {
+    // rows padded by 16 bytes: the 16-byte fragment reads of 32 consecutive rows then fall
+    // on distinct LDS banks
+    bf16_t q[kRowGroup][D + 8];
+    union {
+        bf16_t k[kTile][D + 8];
+        float merge[2][32][kTile + 1];   // per-lane (max, sum) of 32 rows, after the tile loop
+    };
+    float lse[kRowGroup];
+    float acc[kSpan];
+};
+
+template <int D>
+__device__ __forceinline__ void stage_q_bf16(const FcMassArgs& a, int64_t row0, int w0, int nw, int h,
+                                             bf16_t (*qs)[D + 8]) {
+    constexpr int PR = D / 8;   // 16-byte pieces per row
+    for (int i = threadIdx.x; i < kRowGroup * PR; i += kNT) {
+        const int w = i / PR, c = i % PR;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (w < nw)
+            v = *reinterpret_cast<const uint4*>((const bf16_t*)a.q_base +
+                                                ((row0 + w0 + w) * a.H_q + h) * D + c * 8);
+        *reinterpret_cast<uint4*>(&qs[w][c * 8]) = v;
+    }
+}
+
+// 128-key tile -> registers (coalesced: consecutive threads take consecutive 16-byte pieces);
+// rows past mass_len re-read the last valid row and are masked by the callers.
+template <int D>
+__device__ __forceinline__ void fetch_ktile(const FcMassArgs& a, const bf16_t* kh, int j0,
+                                            uint4 (&kr)[D / 16]) {
+    constexpr int PR = D / 8;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) {
+        const int p = threadIdx.x + kNT * i;
+        int j = j0 + p / PR;
+        j = j < a.mass_len ? j : a.mass_len - 1;
+        kr[i] = *reinterpret_cast<const uint4*>(kh + (int64_t)j * a.tok_stride + (p % PR) * 8);
+    }
+}
+template <int D>
+__device__ __forceinline__ void store_ktile(bf16_t (*ks)[D + 8], const uint4 (&kr)[D / 16]) {
+    constexpr int PR = D / 8;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) {
+        const int p = threadIdx.x + kNT * i;
+        *reinterpret_cast<uint4*>(&ks[p / PR][(p % PR) * 8]) = kr[i];
+    }
+}
+
+// S[row][key] for the 64 staged rows and this wavefront's 32 keys of the tile:
+// s[rb][r] = row rb*32 + (r/4)*8 + (lane/32)*4 + r%4, key = wave*32 + lane%32.
+template <int D>
+__device__ __forceinline__ void tile_scores(const MassSmem<D>& sm, int wave, int lane,
+                                            f32x16_t (&s)[2]) {
+    const int n = lane & 31, half = lane >> 5;
+    bf16x8_t kf[D / 16];
+#pragma unroll
+    for (int kb = 0; kb < D / 16; ++kb)
+        kf[kb] = *reinterpret_cast<const bf16x8_t*>(&sm.k[wave * 32 + n][kb * 16 + half * 8]);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        f32x16_t c = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int kb = 0; kb < D / 16; ++kb) {
+            const bf16x8_t qf =
+                *reinterpret_cast<const bf16x8_t*>(&sm.q[rb * 32 + n][kb * 16 + half * 8]);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[kb], c, 0, 0, 0);
+        }
+        s[rb] = c;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kNT) void mass_stats_bf16_kernel(FcMassArgs a, int w0, int nw, int np,
+                                                              float* __restrict__ pm,
+                                                              float* __restrict__ pl) {
+    int64_t row0;
+    if (!resolve_rows(a, row0)) return;
+    __shared__ MassSmem<D> sm;
+    const int h = blockIdx.y;
+    const int hk = h / (a.H_q / a.H_k);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const bf16_t* kh = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
+    const int jb = blockIdx.x * kSpan;
+    const int left = a.mass_len - jb;
+    const int nt = left >= kSpan ? kTilesPerBlock : (left + kTile - 1) / kTile;
+    const float c2 = a.scale * kLog2e;
+    stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
+    uint4 kr[D / 16];
+    fetch_ktile<D>(a, kh, jb, kr);
+    float m[2][16], l[2][16];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { m[rb][r] = kNegBig; l[rb][r] = 0.f; }
+    for (int t = 0; t < nt; ++t) {
+        __syncthreads();
+        store_ktile<D>(sm.k, kr);
+        __syncthreads();
+        if (t + 1 < nt) fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);
+        f32x16_t s[2];
+        tile_scores<D>(sm, wave, lane, s);
+        const bool ok = jb + t * kTile + wave * 32 + (lane & 31) < a.mass_len;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float v = ok ? s[rb][r] * c2 : kNegBig;
+                const float mn = fmaxf(m[rb][r], v);
+                const float e = ok ? __builtin_amdgcn_exp2f(v - mn) : 0.f;
+                l[rb][r] = l[rb][r] * __builtin_amdgcn_exp2f(m[rb][r] - mn) + e;
+                m[rb][r] = mn;
+            }
+    }
+    // merge the 128 per-lane statistics of every row, in a fixed order
+    const int col = wave * 32 + (lane & 31);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            sm.merge[0][row][col] = m[rb][r];
+            sm.merge[1][row][col] = l[rb][r];
+        }
+        __syncthreads();
+        const int row = tid >> 3, part = tid & 7;
+        float mx = kNegBig;
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sm.merge[0][row][part * 16 + i]);
+        float sum = 0.f;
+        for (int i = 0; i < 16; ++i)
+            sum += sm.merge[1][row][part * 16 + i] *
+                   __builtin_amdgcn_exp2f(sm.merge[0][row][part * 16 + i] - mx);
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) {
+            const float mo = __shfl_xor(mx, o, FC_WAVE), so = __shfl_xor(sum, o, FC_WAVE);
+            const float mn = fmaxf(mx, mo);
+            // the lower lane's term first on both sides, so partners agree bit for bit
+            const float lo = (part & o) ? so * __builtin_amdgcn_exp2f(mo - mn)
+                                        : sum * __builtin_amdgcn_exp2f(mx - mn);
+            const float hi = (part & o) ? sum * __builtin_amdgcn_exp2f(mx - mn)
+                                        : so * __builtin_amdgcn_exp2f(mo - mn);
+            sum = lo + hi;
+            mx = mn;
+        }
+        if (part == 0) {
+            pm[((int64_t)h * kRowGroup + rb * 32 + row) * np + blockIdx.x] = mx;
+            pl[((int64_t)h * kRowGroup + rb * 32 + row) * np + blockIdx.x] = sum;
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kNT) void mass_cols_bf16_kernel(FcMassArgs a, int w0, int nw, int np,
+                                                             const float* __restrict__ pm,
+                                                             const float* __restrict__ pl,
+                                                             int first) {
+    const int hk = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int jb = blockIdx.x * kSpan;
+    const int left = a.mass_len - jb;
+    const int nkeys = left >= kSpan ? kSpan : left;
+    int64_t row0;
+    if (!resolve_rows(a, row0)) {
+        for (int i = tid; i < nkeys; i += kNT)
+            a.mass[(int64_t)hk * a.mass_len + jb + i] = __uint_as_float(0x7fc00000u);
+        return;
+    }
+    __shared__ MassSmem<D> sm;
+    const int G = a.H_q / a.H_k;
+    const bf16_t* kh = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
+    const int nt = (nkeys + kTile - 1) / kTile;
+    const float c2 = a.scale * kLog2e;
+    for (int i = tid; i < kSpan; i += kNT) sm.acc[i] = 0.f;
+    for (int g = 0; g < G; ++g) {
+        const int h = hk * G + g;
+        __syncthreads();
+        stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
+        if (tid < kRowGroup) {
+            // log2-sum-exp of row tid over all keys: the blocks' partials in index order
+            const float* m = pm + ((int64_t)h * kRowGroup + tid) * np;
+            const float* l = pl + ((int64_t)h * kRowGroup + tid) * np;
+            float mx = kNegBig;
+            for (int i = 0; i < np; ++i) mx = fmaxf(mx, m[i]);
+            float sum = 0.f;
+            for (int i = 0; i < np; ++i) sum += l[i] * __builtin_amdgcn_exp2f(m[i] - mx);
+            // padding rows get a huge normaliser: their terms vanish
+            sm.lse[tid] = tid < nw ? mx + __builtin_amdgcn_logf(sum) : kPosBig;
+        }
+        uint4 kr[D / 16];
+        fetch_ktile<D>(a, kh, jb, kr);
+        __syncthreads();
+        float lr[2][16];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                lr[rb][r] = sm.lse[rb * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)];
+        for (int t = 0; t < nt; ++t) {
+            __syncthreads();
+            store_ktile<D>(sm.k, kr);
+            __syncthreads();
+            if (t + 1 < nt) fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);
+            f32x16_t s[2];
+            tile_scores<D>(sm, wave, lane, s);
+            float v = 0.f;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v += __builtin_amdgcn_exp2f(s[rb][r] * c2 - lr[rb][r]);
+            v += __shfl_xor(v, 32, FC_WAVE);
+            if (lane < 32) sm.acc[t * kTile + wave * 32 + lane] += v;   // one owner per key
+        }
+    }
+    __syncthreads();
+    const float inv = 1.0f / (float)(a.W * G);
+    for (int i = tid; i < nkeys; i += kNT) {
+        float* dst = a.mass + (int64_t)hk * a.mass_len + jb + i;
+        const float c = sm.acc[i] * inv;
+        *dst = first ? c : *dst + c;
+    }
+}
+
+template <int D>
+int launch_bf16(const FcMassArgs& a, hipStream_t s) {
+    const int np = (a.mass_len + kSpan - 1) / kSpan;
+    float* pm = reinterpret_cast<float*>(a.ws);
+    float* pl = pm + (size_t)a.H_q * kRowGroup * np;
+    for (int w0 = 0; w0 < a.W; w0 += kRowGroup) {
+        const int nw = (a.W - w0 < kRowGroup) ? a.W - w0 : kRowGroup;
+        mass_stats_bf16_kernel<D><<<dim3(np, a.H_q), kNT, 0, s>>>(a, w0, nw, np, pm, pl);
+        FC_LAUNCH_CHECK();
+        mass_cols_bf16_kernel<D><<<dim3(np, a.H_k), kNT, 0, s>>>(a, w0, nw, np, pm, pl, w0 == 0 ? 1 : 0);
+        FC_LAUNCH_CHECK();
+    }
+    return FC_OK;
+}
+
 template <typename T, int D>
 int launch_typed(const FcMassArgs& a, hipStream_t s) {
     const int nkb = (a.mass_len + kKeys - 1) / kKeys;
@@ -182,8 +437,8 @@ size_t fc_mass_workspace(int W, int H_q, int mass_len) {
 
 int fc_launch_mass(const FcMassArgs& a, hipStream_t s) {
     if (a.dtype == FC_BF16) {
-        if (a.d == 128) return launch_typed<bf16_t, 128>(a, s);
-        if (a.d == 64) return launch_typed<bf16_t, 64>(a, s);
+        if (a.d == 128) return launch_bf16<128>(a, s);
+        if (a.d == 64) return launch_bf16<64>(a, s);
     } else {
         if (a.d == 128) return launch_typed<float, 128>(a, s);
         if (a.d == 64) return launch_typed<float, 64>(a, s);
