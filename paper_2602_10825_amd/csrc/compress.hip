@@ -40,29 +40,28 @@ constexpr int kBins = 1 << kDigitBits;
 constexpr int kCand = 4096;   // candidates resolved in LDS
 constexpr int kUnroll = 8;    // independent loads in flight per thread in the selection scans
 
-// ---- per-lane slice of one token row, widened exactly to float64 ---------------------
+// ---- per-lane slice of one token row: raw bits held in registers, widened exactly ------
 template <typename T, int D>
-__device__ __forceinline__ void load_slice(const T* row, int u, double (&x)[D / 16]) {
-    constexpr int EL = D / 16;
-    const T* p = row + u * EL;
-    if constexpr (sizeof(T) == 2 && EL == 8) {
-        const uint4 v = *reinterpret_cast<const uint4*>(p);
-        float f[8];
-        unpack16(v, f, bf16_t());
+struct Slice {
+    static constexpr int EL = D / 16;                       // elements per lane
+    static constexpr int NW = EL * (int)sizeof(T) / 4;      // 32-bit words per lane
+    typedef uint32_t raw_t __attribute__((ext_vector_type(NW)));
+    static __device__ __forceinline__ raw_t load(const T* row, int u) {
+        return *reinterpret_cast<const raw_t*>(row + u * EL);
+    }
+    static __device__ __forceinline__ void widen(const raw_t& r, double (&x)[EL]) {
+        if constexpr (sizeof(T) == 2) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = (double)f[e];
-    } else if constexpr (sizeof(T) == 2 && EL == 4) {
-        const uint2 v = *reinterpret_cast<const uint2*>(p);
-        x[0] = (double)bf16lo_to_f32(v.x); x[1] = (double)bf16hi_to_f32(v.x);
-        x[2] = (double)bf16lo_to_f32(v.y); x[3] = (double)bf16hi_to_f32(v.y);
-    } else {
+            for (int w = 0; w < NW; ++w) {
+                x[2 * w] = (double)bf16lo_to_f32(r[w]);
+                x[2 * w + 1] = (double)bf16hi_to_f32(r[w]);
+            }
+        } else {
 #pragma unroll
-        for (int e = 0; e < EL; e += 4) {
-            const float4 v = *reinterpret_cast<const float4*>(p + e);
-            x[e] = (double)v.x; x[e + 1] = (double)v.y; x[e + 2] = (double)v.z; x[e + 3] = (double)v.w;
+            for (int w = 0; w < NW; ++w) x[w] = (double)__uint_as_float(r[w]);
         }
     }
-}
+};
 
 // all-reduce over the 16 lanes of a group; every lane ends with identical bits
 __device__ __forceinline__ double group_sum(double v) {
@@ -73,29 +72,52 @@ __device__ __forceinline__ double group_sum(double v) {
     return v;
 }
 
+// A group of 16 lanes takes 16 consecutive tokens per round: all 16 row slices are loaded
+// first (16 loads in flight per lane), the norms are all-reduced over the group, and lane u
+// finishes token u (square root, reciprocal, the token's record) -- one token per lane
+// instead of every lane repeating the same float64 work.
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void key_stats_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
     double2* __restrict__ tokinfo, double* __restrict__ psum) {
-    constexpr int EL = D / 16;
+    typedef Slice<T, D> S;
+    constexpr int EL = S::EL;
     const int h = blockIdx.y;
     const int g = threadIdx.x / 16, u = threadIdx.x % 16;
     const T* base = k_cache + (int64_t)h * head_stride;
     double acc[EL];
 #pragma unroll
     for (int e = 0; e < EL; ++e) acc[e] = 0.0;
-    for (int j = blockIdx.x * kGroups + g; j < L; j += gridDim.x * kGroups) {
-        double x[EL];
-        load_slice<T, D>(base + (int64_t)j * tok_stride, u, x);
-        double n2 = 0.0;
+    for (int j0 = (blockIdx.x * kGroups + g) * 16; j0 < L; j0 += gridDim.x * kGroups * 16) {
+        typename S::raw_t raw[16];
 #pragma unroll
-        for (int e = 0; e < EL; ++e) n2 = fma(x[e], x[e], n2);
-        n2 = group_sum(n2);
-        const double nrm = sqrt(n2);
-        const double inv = 1.0 / fmax(nrm, 1e-12);
-        if (u == 0) tokinfo[(int64_t)h * L + j] = make_double2(inv, (n2 * inv) * inv);
+        for (int i = 0; i < 16; ++i) {
+            const int j = j0 + i;
+            raw[i] = S::load(base + (int64_t)(j < L ? j : L - 1) * tok_stride, u);
+        }
+        double mine = 0.0;
 #pragma unroll
-        for (int e = 0; e < EL; ++e) acc[e] += x[e] * inv;
+        for (int i = 0; i < 16; ++i) {
+            double x[EL];
+            S::widen(raw[i], x);
+            double n2 = 0.0;
+#pragma unroll
+            for (int e = 0; e < EL; ++e) n2 = fma(x[e], x[e], n2);
+            n2 = group_sum(n2);
+            mine = (i == u) ? n2 : mine;
+        }
+        const double inv_mine = 1.0 / fmax(sqrt(mine), 1e-12);
+        if (j0 + u < L) tokinfo[(int64_t)h * L + j0 + u] = make_double2(inv_mine, (mine * inv_mine) * inv_mine);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            double inv = __shfl(inv_mine, i, 16);
+            inv = (j0 + i < L) ? inv : 0.0;   // rows past the end were re-reads of the last row
+            double x[EL];
+            asm volatile("" : "+v"(raw[i]));   // widen again here rather than keep 16 rows of doubles live
+            S::widen(raw[i], x);
+#pragma unroll
+            for (int e = 0; e < EL; ++e) acc[e] += x[e] * inv;
+        }
     }
     __shared__ double sh[kGroups][D];
 #pragma unroll
@@ -141,7 +163,8 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
     const double2* __restrict__ tokinfo, const double* __restrict__ ssum,
     double* __restrict__ e_out, double* __restrict__ pz) {
-    constexpr int EL = D / 16;
+    typedef Slice<T, D> S;
+    constexpr int EL = S::EL;
     const int h = blockIdx.y;
     const int g = threadIdx.x / 16, u = threadIdx.x % 16;
     const T* base = k_cache + (int64_t)h * head_stride;
@@ -150,28 +173,41 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     for (int e = 0; e < EL; ++e) s[e] = ssum[h * D + u * EL + e];
     const double dL = (double)L;
     double zsum = 0.0;
-    for (int j = blockIdx.x * kGroups + g; j < L; j += gridDim.x * kGroups) {
-        double x[EL];
-        load_slice<T, D>(base + (int64_t)j * tok_stride, u, x);
-        double dot = 0.0;
+    // 16 consecutive tokens per group and round, as in key_stats; lane u exponentiates token u
+    for (int j0 = (blockIdx.x * kGroups + g) * 16; j0 < L; j0 += gridDim.x * kGroups * 16) {
+        typename S::raw_t raw[16];
 #pragma unroll
-        for (int e = 0; e < EL; ++e) dot = fma(x[e], s[e], dot);
-        dot = group_sum(dot);
-        if (u == 0) {
-            const double2 ti = tokinfo[(int64_t)h * L + j];
-            const double ej = exp((dot * ti.x - ti.y) / dL);
-            e_out[(int64_t)h * L + j] = ej;
+        for (int i = 0; i < 16; ++i) {
+            const int j = j0 + i;
+            raw[i] = S::load(base + (int64_t)(j < L ? j : L - 1) * tok_stride, u);
+        }
+        const bool have = j0 + u < L;
+        const double2 ti = tokinfo[(int64_t)h * L + (have ? j0 + u : L - 1)];
+        double mine = 0.0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            double x[EL];
+            S::widen(raw[i], x);
+            double dot = 0.0;
+#pragma unroll
+            for (int e = 0; e < EL; ++e) dot = fma(x[e], s[e], dot);
+            dot = group_sum(dot);
+            mine = (i == u) ? dot : mine;
+        }
+        if (have) {
+            const double ej = exp((mine * ti.x - ti.y) / dL);
+            e_out[(int64_t)h * L + j0 + u] = ej;
             zsum += ej;
         }
     }
-    __shared__ double shz[kGroups];
-    if (u == 0) shz[g] = zsum;
+    __shared__ double shz[kThreads];
+    shz[threadIdx.x] = zsum;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        double z = 0.0;
+    if (threadIdx.x < 64) {   // fixed order: four strided terms per lane, then the lanes in order
+        double z = (shz[threadIdx.x] + shz[threadIdx.x + 64]) + (shz[threadIdx.x + 128] + shz[threadIdx.x + 192]);
 #pragma unroll
-        for (int k = 0; k < kGroups; ++k) z += shz[k];
-        pz[(int64_t)h * gridDim.x + blockIdx.x] = z;
+        for (int o = 32; o > 0; o >>= 1) z += __shfl_down(z, o, FC_WAVE);
+        if (threadIdx.x == 0) pz[(int64_t)h * gridDim.x + blockIdx.x] = z;
     }
 }
 
@@ -579,7 +615,7 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(
     const int row0 = tile * kTileRows;
     const int lrow = tid / VPR, lcol = tid % VPR;
 
-    uint4 kr[LDN], vr[LDN];
+    u32x4_native kr[LDN], vr[LDN];   // native vectors: the arrays stay in registers
     int src[LDN];
 #pragma unroll
     for (int p = 0; p < LDN; ++p) {
@@ -588,8 +624,8 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(
         if (src[p] >= L) src[p] = -1;   // never read outside the compressed range
         if (src[p] >= 0 && src[p] != s) {
             const int64_t a = h * head_stride_v + (int64_t)src[p] * tok_stride_v + lcol;
-            kr[p] = k_cache[a];
-            vr[p] = v_cache[a];
+            kr[p] = *reinterpret_cast<const u32x4_native*>(k_cache + a);
+            vr[p] = *reinterpret_cast<const u32x4_native*>(v_cache + a);
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the rows are in registers
@@ -618,8 +654,8 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(
         const int s = row0 + p * RPP + lrow;
         if (src[p] >= 0 && src[p] != s) {
             const int64_t a = h * head_stride_v + (int64_t)s * tok_stride_v + lcol;
-            k_cache[a] = kr[p];
-            v_cache[a] = vr[p];
+            *reinterpret_cast<u32x4_native*>(k_cache + a) = kr[p];
+            *reinterpret_cast<u32x4_native*>(v_cache + a) = vr[p];
         }
     }
 }
@@ -631,7 +667,7 @@ struct WsLayout {
 
 WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     WsLayout w;
-    int nblk = (L + kGroups * 8 - 1) / (kGroups * 8);
+    int nblk = (L + kGroups * 16 - 1) / (kGroups * 16);   // one round of 16 tokens per group
     const int cap = 2048 / (H > 0 ? H : 1);
     if (nblk > cap) nblk = cap;
     if (nblk < 1) nblk = 1;

@@ -198,23 +198,23 @@ __device__ __forceinline__ void stage_q_bf16(const FcMassArgs& a, int64_t row0, 
 // rows past mass_len re-read the last valid row and are masked by the callers.
 template <int D>
 __device__ __forceinline__ void fetch_ktile(const FcMassArgs& a, const bf16_t* kh, int j0,
-                                            uint4 (&kr)[D / 16]) {
+                                            u32x4_native (&kr)[D / 16]) {
     constexpr int PR = D / 8;
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) {
         const int p = threadIdx.x + kNT * i;
         int j = j0 + p / PR;
         j = j < a.mass_len ? j : a.mass_len - 1;
-        kr[i] = *reinterpret_cast<const uint4*>(kh + (int64_t)j * a.tok_stride + (p % PR) * 8);
+        kr[i] = *reinterpret_cast<const u32x4_native*>(kh + (int64_t)j * a.tok_stride + (p % PR) * 8);
     }
 }
 template <int D>
-__device__ __forceinline__ void store_ktile(bf16_t (*ks)[D + 8], const uint4 (&kr)[D / 16]) {
+__device__ __forceinline__ void store_ktile(bf16_t (*ks)[D + 8], const u32x4_native (&kr)[D / 16]) {
     constexpr int PR = D / 8;
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) {
         const int p = threadIdx.x + kNT * i;
-        *reinterpret_cast<uint4*>(&ks[p / PR][(p % PR) * 8]) = kr[i];
+        *reinterpret_cast<u32x4_native*>(&ks[p / PR][(p % PR) * 8]) = kr[i];
     }
 }
 
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kNT) void mass_stats_bf16_kernel(FcMassArgs a, int 
     const int nt = left >= kSpan ? kTilesPerBlock : (left + kTile - 1) / kTile;
     const float c2 = a.scale * kLog2e;
     stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
-    uint4 kr[D / 16];
+    u32x4_native kr[D / 16];
     fetch_ktile<D>(a, kh, jb, kr);
     float m[2][16], l[2][16];
 #pragma unroll
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kNT) void mass_stats_bf16_kernel(FcMassArgs a, int 
         __syncthreads();
         store_ktile<D>(sm.k, kr);
         __syncthreads();
-        if (t + 1 < nt) fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);
+        fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);   // past the end: clamped, unused
         f32x16_t s[2];
         tile_scores<D>(sm, wave, lane, s);
         const bool ok = jb + t * kTile + wave * 32 + (lane & 31) < a.mass_len;
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(kNT) void mass_cols_bf16_kernel(FcMassArgs a, int w
             // padding rows get a huge normaliser: their terms vanish
             sm.lse[tid] = tid < nw ? mx + __builtin_amdgcn_logf(sum) : kPosBig;
         }
-        uint4 kr[D / 16];
+        u32x4_native kr[D / 16];
         fetch_ktile<D>(a, kh, jb, kr);
         __syncthreads();
         float lr[2][16];
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(kNT) void mass_cols_bf16_kernel(FcMassArgs a, int w
             __syncthreads();
             store_ktile<D>(sm.k, kr);
             __syncthreads();
-            if (t + 1 < nt) fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);
+            fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);   // past the end: clamped, unused
             f32x16_t s[2];
             tile_scores<D>(sm, wave, lane, s);
             float v = 0.f;
