@@ -1,0 +1,119 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times
+(decide + gather, scatter of new K/V, attention without fused scatter, stand-alone
+importance mass, compression): element-wise where the fp64 oracle finishes in seconds
+(decide, mass, compression), on sampled query rows for attention, plus properties that
+hold for every output row."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flowcache_oracle as O
+from paper_2602_10825_amd import binding as B
+from paper_2602_10825_amd import synth
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+DEV = "cuda"
+
+
+def sample_rows(wl, per_chunk, seed):
+    """First/last rows, rows either side of the 32- and 256-row tile edges, random others."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for c in range(wl.A):
+        pick = {0, 31, 32, 255, 256, wl.L_c - 257, wl.L_c - 1}
+        pick |= set(rng.integers(0, wl.L_c, size=per_chunk).tolist())
+        rows += [c * wl.L_c + r for r in sorted(pick)[:per_chunk + 7] if 0 <= r < wl.L_c]
+    return rows
+
+
+@pytest.mark.parametrize("wl,per_chunk,heads", [
+    (synth.C2, 24, None),                 # all 12 heads
+    (synth.C3, 6, [0, 7, 16, 23]),
+])
+def test_full_size_step_matches_oracle(wl, per_chunk, heads):
+    print(f"full-size step: {wl.name}", flush=True)
+    d = synth.decide_inputs(wl, seed=0)
+    a = synth.attend_inputs(wl, seed=0)
+    A, L_c = wl.A, wl.L_c
+    rec = list(range(A))
+
+    # ---- change metric + decision + gather: the paper's threshold, then eps = 0 --------
+    xc, xp = B.to_device(d["x_cur"], wl.dtype, DEV), B.to_device(d["x_prev"], wl.dtype, DEV)
+    step = torch.from_numpy(d["step_idx"]).to(DEV)
+    masks = []
+    for eps in (wl.eps, 0.05, 0.0):
+        acc = torch.from_numpy(d["acc"].copy()).to(DEV)
+        out = B.flowcache_chunk_decide(xc, xp, step, wl.warmup_m, eps, acc, gather=True)
+        ref = O.chunk_decide(d["x_cur"], d["x_prev"], d["step_idx"], wl.warmup_m, eps, d["acc"])
+        assert ref["margin"].min() > 1e-9
+        assert out["recompute_mask"].cpu().numpy().tolist() == ref["mask"].tolist()
+        masks.append(ref["mask"].tolist())
+        n = int(out["n_recompute"].item())
+        assert out["recompute_idx"].cpu().numpy()[:n].tolist() == ref["recompute_idx"].tolist()
+        assert np.allclose(out["l1rel"].cpu().numpy(), ref["l1rel"], rtol=1e-12, atol=0)
+        assert np.allclose(acc.cpu().numpy(), ref["acc"], rtol=1e-12, atol=0)
+        xcomp = B.to_host(out["x_compact"])
+        for r, c in enumerate(ref["recompute_idx"].tolist()):
+            assert np.array_equal(xcomp[r], d["x_cur"][c])
+    assert n == A                                          # eps = 0: every chunk recomputes
+    assert any(0 in mk for mk in masks)                    # and the thresholds do skip chunks
+    idx, n_rec = out["recompute_idx"], out["n_recompute"]
+    del xc, xp, xcomp
+
+    # ---- scatter of the new K/V, then attention reading the cache ---------------------
+    print("  attention", flush=True)
+    kc, vc = B.to_device(a["k_cache"], wl.dtype, DEV), B.to_device(a["v_cache"], wl.dtype, DEV)
+    B.flowcache_scatter_kv(B.to_device(a["k_new"], wl.dtype, DEV), B.to_device(a["v_new"], wl.dtype, DEV),
+                           kc, vc, L_c, wl.L_clean, a["active_off"], idx, n_rec)
+    kc_ref = O.scatter_kv(a["k_cache"], a["k_new"], rec, a["active_off"], L_c)
+    vc_ref = O.scatter_kv(a["v_cache"], a["v_new"], rec, a["active_off"], L_c)
+    assert np.array_equal(B.to_host(kc), kc_ref) and np.array_equal(B.to_host(vc), vc_ref)
+    q = B.to_device(a["q"], wl.dtype, DEV)
+    res = B.flowcache_attend(q, None, None, kc, vc, L_c, wl.L_clean, a["active_off"], idx, n_rec)
+    torch.cuda.synchronize()
+    rows = sample_rows(wl, per_chunk, seed=1)
+    hs = list(range(wl.H_q)) if heads is None else heads
+    ref_out, ref_lse = O.attend(a["q"], kc_ref, vc_ref, wl.L_clean, a["active_off"], L_c, rec,
+                                rows=rows, heads=hs)
+    got_all = res["out"]
+    got = O.widen(B.to_host(got_all[rows][:, hs].contiguous()))
+    err = np.abs(got - ref_out)
+    assert err.max() <= 2e-2
+    assert np.sqrt((err ** 2).sum()) / np.sqrt((ref_out ** 2).sum()) <= 1e-2
+    lse = res["lse"][hs][:, rows].cpu().numpy()
+    assert np.abs(lse - ref_lse).max() <= 2e-2
+    # every output row: finite and inside the per-coordinate range of its visible values
+    of = got_all.float().view(A, L_c, wl.H_q, wl.d)
+    assert torch.isfinite(of).all()
+    vf = vc.float()                  # [H_k, capacity, d]
+    G = wl.H_q // wl.H_k
+    lo = vf[:, :wl.L_clean].amin(1)
+    hi = vf[:, :wl.L_clean].amax(1)
+    for c in range(A):
+        o0 = int(a["active_off"][c])
+        lo = torch.minimum(lo, vf[:, o0:o0 + L_c].amin(1))
+        hi = torch.maximum(hi, vf[:, o0:o0 + L_c].amax(1))
+        loq, hiq = lo.repeat_interleave(G, 0), hi.repeat_interleave(G, 0)
+        assert (of[c] >= loq - 1e-2).all() and (of[c] <= hiq + 1e-2).all()
+    del of, vf, got_all
+
+    # ---- importance mass of the first L_k keys: the whole tensor against the oracle ----
+    print("  mass", flush=True)
+    W, L_k = wl.obs_window, wl.L_k
+    q_obs = np.ascontiguousarray(a["q"][A * L_c - W:])
+    mass = B.flowcache_attention_mass(B.to_device(q_obs, wl.dtype, DEV), kc, L_k)
+    ref_mass = O.attention_mass(q_obs, kc_ref, L_k)
+    m = mass.cpu().numpy().astype(np.float64)
+    assert np.all(m >= 0) and np.allclose(m.sum(1), 1.0, atol=1e-4)
+    assert (np.abs(m - ref_mass).sum(1) / ref_mass.sum(1)).max() <= 1e-2
+
+    # ---- compression from the same mass bits: kept indices and both caches bit-exact ----
+    print("  compression", flush=True)
+    kept = B.flowcache_kv_compress(kc, vc, L_k, wl.budget, mass, wl.pool_k, wl.lam)
+    torch.cuda.synchronize()
+    rk, rk_k, rk_v, sc = O.kv_compress(kc_ref, vc_ref, L_k, wl.budget, mass.cpu().numpy(),
+                                       wl.pool_k, wl.lam)
+    gaps = [O.boundary_gap(sc[h], wl.budget) for h in range(wl.H_k)]
+    assert all(g == 0.0 or g > 1e-12 for g in gaps), f"ambiguous boundary {gaps}"
+    assert np.array_equal(kept.cpu().numpy(), rk)
+    assert np.array_equal(B.to_host(kc), rk_k) and np.array_equal(B.to_host(vc), rk_v)
