@@ -1,0 +1,75 @@
+"""Long-rollout cache maintenance (Sec. 3.3, App. B): chunk after chunk is committed to a
+budgeted clean cache; while it fits the cache only grows, afterwards every commit merges
+[compressed cache | finished chunk] and compresses back to the budget.  The GPU cache and a
+host mirror run side by side; at every commit the importance mass emitted by the GPU is
+compared with the oracle's by tolerance and then fed to BOTH compressions (shared-mass
+protocol), whose kept-index arrays and caches must agree bit for bit -- so the two sides
+hold identical caches all the way through."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import flowcache_oracle as O
+from paper_2602_10825_amd import binding as B
+from paper_2602_10825_amd import synth
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1800)]
+DEV = "cuda"
+
+# MAGI-1-like head shape; the default run keeps the cache at 4 chunks and commits 10, the
+# long run (FLOWCACHE_LONG_ROLLOUT=1) is 64 commits at a 16-chunk budget.
+LONG = os.environ.get("FLOWCACHE_LONG_ROLLOUT", "0") == "1"
+
+
+@pytest.mark.parametrize("wl,budget_chunks,commits", [
+    (synth.MID_BF16, 3, 9),
+    (synth.C3, 16, 64) if LONG else (synth.C3, 4, 10),
+])
+def test_commit_sequence_keeps_identical_caches(wl, budget_chunks, commits):
+    H, L_c, d, W = wl.H_k, wl.L_c, wl.d, wl.obs_window
+    budget = budget_chunks * L_c
+    cap = budget + L_c
+    k_ref = np.zeros((H, cap, d), np.uint16)
+    v_ref = np.zeros((H, cap, d), np.uint16)
+    k_gpu = torch.zeros((H, cap, d), dtype=torch.bfloat16, device=DEV)
+    v_gpu = torch.zeros_like(k_gpu)
+    length = 0
+    compressed = 0
+    for commit in range(commits):
+        earlier = O.widen(k_ref[:, :length]).astype(np.float32) if length else None
+        k_new, v_new = synth.rollout_chunk_keys(wl, seed=7, commit=commit, earlier=earlier)
+        k_ref[:, length:length + L_c] = k_new
+        v_ref[:, length:length + L_c] = v_new
+        k_gpu[:, length:length + L_c] = B.to_device(k_new, "bf16", DEV)
+        v_gpu[:, length:length + L_c] = B.to_device(v_new, "bf16", DEV)
+        merged = length + L_c
+        if merged <= budget:                              # cache-filling phase: append only
+            kept = B.flowcache_kv_compress(k_gpu, v_gpu, merged, budget,
+                                           torch.zeros((H, merged), device=DEV), wl.pool_k, wl.lam)
+            assert np.array_equal(kept.cpu().numpy(), np.tile(np.arange(merged, dtype=np.int32), (H, 1)))
+            assert np.array_equal(B.to_host(k_gpu), k_ref)
+            length = merged
+            continue
+        q_obs = synth.observation_queries(wl, seed=7, commit=commit, W=W)
+        mass = B.flowcache_attention_mass(B.to_device(q_obs, "bf16", DEV), k_gpu, merged)
+        ref_mass = O.attention_mass(q_obs, k_ref, merged)
+        m = mass.cpu().numpy()
+        rel = np.abs(m.astype(np.float64) - ref_mass).sum(1) / ref_mass.sum(1)
+        assert rel.max() <= 1e-2, (commit, rel.max())
+        kept = B.flowcache_kv_compress(k_gpu, v_gpu, merged, budget, mass, wl.pool_k, wl.lam)
+        torch.cuda.synchronize()
+        rk, k_ref, v_ref, sc = O.kv_compress(k_ref, v_ref, merged, budget, m, wl.pool_k, wl.lam)
+        gaps = [O.boundary_gap(sc[h], budget) for h in range(H)]
+        assert all(g == 0.0 or g > 1e-12 for g in gaps), (commit, gaps)
+        assert np.array_equal(kept.cpu().numpy(), rk), commit
+        assert np.array_equal(B.to_host(k_gpu[:, :budget]), k_ref[:, :budget]), commit
+        assert np.array_equal(B.to_host(v_gpu[:, :budget]), v_ref[:, :budget]), commit
+        # survivors of earlier commits thin out, but every generation is still represented
+        assert rk.min() >= 0 and rk.max() < merged and np.all(np.diff(rk, axis=1) > 0)
+        length = budget
+        compressed += 1
+        print(f"  commit {commit}: merged {merged} -> {budget}, new-chunk share "
+              f"{(rk >= budget).mean():.3f}", flush=True)
+    assert compressed == commits - budget_chunks
