@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--workload", default="C2", choices=["C2", "C3", "mid"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
     ap.add_argument("--cpu-rows", type=int, default=256, help="oracle attention rows per chunk")
+    ap.add_argument("--qkv", default="normal", choices=["normal", "const"],
+                    help="const: constant Q/K/V (same instruction stream, full clocks) -- shows how "
+                         "much of the attention time is the power limit; not a valid bench result")
     return ap.parse_args()
 
 
@@ -134,6 +137,8 @@ def main():
     out = torch.empty_like(q)
     k0 = B.to_device(a["k_cache"], wl.dtype, dev)
     v0 = B.to_device(a["v_cache"], wl.dtype, dev)
+    if args.qkv == "const":
+        q.fill_(0.125); k_new.fill_(0.5); v_new.fill_(1.0); k0.fill_(0.5); v0.fill_(1.0)
     k_sets = [k0] + [k0.clone() for _ in range(nset - 1)]   # a fresh cache for every step:
     v_sets = [v0] + [v0.clone() for _ in range(nset - 1)]   # compression is destructive
     active_off = a["active_off"]
@@ -205,7 +210,7 @@ def main():
         "unit": "TFLOP/s (attention FLOPs / whole-step time)",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
+        "dtype": wl.dtype, "data": "synthetic" if args.qkv == "normal" else "synthetic-constant-qkv (NOT a bench result)",
         "config": {"workload": wl.name, "H_q": wl.H_q, "H_k": wl.H_k, "d": wl.d, "A": wl.A,
                    "L_c": wl.L_c, "L_clean": wl.L_clean, "budget": wl.budget, "eps": 0.0,
                    "recompute": "all chunks", "obs_window": Wobs, "pool_k": wl.pool_k,

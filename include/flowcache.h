@@ -8,6 +8,12 @@
  *   flowcache_chunk_decide    per-chunk relative-L1 change metric, accumulate-and-threshold
  *                             reuse decision and gather of the chunks to recompute
  *                             (Sec. 3.2, Eq. (5) and Eq. (8)).
+ *   flowcache_uniform_decide  the uniform ("traditional reuse") policy the paper compares with:
+ *                             one shared accumulator and decision for all chunks past
+ *                             warm-up (Fig. 2, top).
+ *   flowcache_residual_apply  cached-activation reuse around the skipped forward pass:
+ *                             recompute chunks store (output - input), reused chunks get
+ *                             input + stored difference; compact -> full layout (Sec. 3.2).
  *   flowcache_attend          chunk-causal multi-head attention of the recompute chunks
  *                             against [clean KV cache | active chunks' KV], optionally
  *                             emitting the per-key attention mass (Sec. 3.3, Eq. (9)).
@@ -98,6 +104,53 @@ int flowcache_chunk_decide(const void* x_cur, const void* x_prev, fc_dtype dtype
                            int32_t* recompute_idx, int32_t* n_recompute, void* x_compact,
                            void* workspace, size_t workspace_bytes, fc_stream stream);
 size_t flowcache_chunk_decide_workspace(int A, int64_t chunk_elems);
+
+/*
+ * Uniform reuse policy (Fig. 2, top: the policy the chunkwise one is compared with): the relative L1
+ * change is taken over ALL chunks past warm-up together,
+ *
+ *   L1rel = sum_{i: step_idx[i] >= m} sum|x_cur[i] - x_prev[i]| / sum_{i: ...} sum|x_prev[i]|,
+ *   a = acc_global + L1rel;  f = (a > eps) ? 0 : a;  acc_global <- f,
+ *
+ * every such chunk recomputes iff f == 0, and a chunk still in warm-up always recomputes.
+ * With no chunk past warm-up acc_global is reset to 0 and *l1rel is NaN.
+ * Arguments as for flowcache_chunk_decide except
+ *   acc_global [dev] [1] float64 in/out,   l1rel [dev] [1] float64 out, may be NULL.
+ * Uses the same workspace size as flowcache_chunk_decide.
+ */
+int flowcache_uniform_decide(const void* x_cur, const void* x_prev, fc_dtype dtype, int A,
+                             int64_t chunk_elems, const int32_t* step_idx, int warmup_m,
+                             double eps, double* acc_global, double* l1rel,
+                             uint8_t* recompute_mask, int32_t* recompute_idx,
+                             int32_t* n_recompute, void* x_compact, void* workspace,
+                             size_t workspace_bytes, fc_stream stream);
+
+/*
+ * Cached-activation reuse (Sec. 3.2: when f != 0 the cached activations are reused instead
+ * of the forward pass).  The cache holds, per active chunk, the difference between the
+ * stack's output and its input at the chunk's last recompute:
+ *
+ *   chunk c = recompute_idx[r], r < *n_recompute:  residual[c] <- y_compact[r] - x_cur[c]
+ *                                                  out[c]      <- y_compact[r]
+ *   any other chunk c:                             out[c]      <- x_cur[c] + residual[c]
+ *
+ * Operands are widened exactly to float64, the sum or difference is taken in float64 and
+ * rounded ONCE (to nearest even) to `dtype`.
+ *
+ *   x_cur      [dev] [A, chunk_elems] input of the stack this tick
+ *   y_compact  [dev] [A, chunk_elems] compact: block r = output for chunk recompute_idx[r]
+ *                    (blocks r >= *n_recompute are not read); may be NULL only if the
+ *                    caller guarantees *n_recompute == 0
+ *   residual   [dev] [A, chunk_elems] in/out cache
+ *   out        [dev] [A, chunk_elems] full-layout output of the stack; may alias x_cur
+ *   recompute_idx, n_recompute [dev] as written by the decide calls
+ * Errors: null pointers (except y_compact), A outside [1, FC_MAX_ACTIVE], chunk_elems < 1
+ * -> FC_INVALID_ARGUMENT.
+ */
+int flowcache_residual_apply(const void* x_cur, const void* y_compact, void* residual, void* out,
+                             fc_dtype dtype, int A, int64_t chunk_elems,
+                             const int32_t* recompute_idx, const int32_t* n_recompute,
+                             fc_stream stream);
 
 /*
  * Chunk-causal attention of the recompute chunks.  Sec. 3.3 (clean chunks live in the KV

@@ -11,6 +11,10 @@ special cases) live in ``tests/test_oracle_*.py``.  Pin status:
 
   relative_l1, reuse_policy, chunk_decide .. pinned (hand-worked case, closed forms)
   gather_chunks, scatter_kv ................ pinned (exact copies)
+  narrow, residual_apply ................... pinned (brute-force nearest neighbour, ties,
+                                             exact round trips, hand-worked case)
+  uniform_decide ........................... pinned (hand-worked case, reduction to the
+                                             chunkwise policy for one chunk)
   attend, attention_mass ................... pinned (brute force loops, library special
                                              case, invariants)
   maxpool1d ................................ pinned (library max-pool, brute force)
@@ -119,6 +123,46 @@ def uniform_decide(x_cur, x_prev, step_idx, warmup_m, eps, acc_global):
     for i in old:
         mask[i] = 1 if f_new == 0.0 else 0
     return {"mask": mask, "acc": f_new, "l1rel": l1}
+
+
+def narrow(x: np.ndarray, like: np.ndarray) -> np.ndarray:
+    """Round float64 values ONCE, to nearest with ties to even, to the storage type of
+    ``like``: float32, or bfloat16 returned as uint16 bit patterns (8 significant bits, the
+    exponent range of float32, gradual underflow below 2^-126)."""
+    x = np.asarray(x, dtype=np.float64)
+    if np.asarray(like).dtype != np.uint16:
+        return x.astype(np.float32)
+    _, e = np.frexp(x)                                # x = m * 2^e, 0.5 <= |m| < 1
+    ulp_exp = np.maximum(e - 8, -133)                 # spacing of bfloat16 numbers around x
+    q = np.rint(np.ldexp(x, -ulp_exp))                # np.rint rounds halves to even
+    y = np.ldexp(q, ulp_exp).astype(np.float32)       # exact: at most 8 significant bits
+    return (y.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+# ======================================================================================
+# Cached-activation reuse around a skipped forward pass -- Sec. 3.2 (text after Eq. (8))
+# ======================================================================================
+def residual_apply(x_cur: np.ndarray, y_compact: Optional[np.ndarray], residual: np.ndarray,
+                   recompute_idx: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+    """Returns (new residual cache, full-layout output).
+
+    The paper only says that a chunk with f != 0 reuses its cached activations.  Reading:
+    the cached quantity is output minus input of the layer stack at the chunk's last
+    recompute (inputs and outputs stay close along the trajectory, Sec. 3.2, third
+    observation), so a reused chunk returns input + cached difference.  Each value is
+    computed in float64 and rounded once to the storage type.
+    """
+    res = np.array(residual, copy=True)
+    out = np.empty_like(np.asarray(x_cur))
+    rec = [int(c) for c in recompute_idx]
+    for c in range(x_cur.shape[0]):
+        if c in rec:
+            r = rec.index(c)
+            res[c] = narrow(widen(y_compact[r]) - widen(x_cur[c]), x_cur)
+            out[c] = y_compact[r]
+        else:
+            out[c] = narrow(widen(x_cur[c]) + widen(residual[c]), x_cur)
+    return res, out
 
 
 # ======================================================================================

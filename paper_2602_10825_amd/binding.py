@@ -24,6 +24,7 @@ FC_MAX_ACTIVE = 16
 EXPORTS = (
     "flowcache_status_string", "flowcache_version",
     "flowcache_chunk_decide", "flowcache_chunk_decide_workspace",
+    "flowcache_uniform_decide", "flowcache_residual_apply",
     "flowcache_attend", "flowcache_attend_workspace", "flowcache_scatter_kv",
     "flowcache_attention_mass", "flowcache_attention_mass_workspace",
     "flowcache_kv_compress", "flowcache_kv_compress_workspace",
@@ -59,6 +60,10 @@ def lib() -> ctypes.CDLL:
     L.flowcache_chunk_decide.restype = c_int
     L.flowcache_chunk_decide.argtypes = [c_vp, c_vp, c_int, c_int, c_i64, c_vp, c_int, c_d, c_vp,
                                          c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    L.flowcache_uniform_decide.restype = c_int
+    L.flowcache_uniform_decide.argtypes = L.flowcache_chunk_decide.argtypes
+    L.flowcache_residual_apply.restype = c_int
+    L.flowcache_residual_apply.argtypes = [c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_i64, c_vp, c_vp, c_vp]
     L.flowcache_attend_workspace.restype = c_sz
     L.flowcache_attend_workspace.argtypes = [c_int] * 7
     L.flowcache_attend.restype = c_int
@@ -140,6 +145,54 @@ def flowcache_chunk_decide(x_cur: torch.Tensor, x_prev: torch.Tensor, step_idx: 
     _check("flowcache_chunk_decide", st)
     return {"recompute_mask": mask, "recompute_idx": idx, "n_recompute": n_rec, "l1rel": l1rel,
             "acc": acc, "x_compact": x_compact}
+
+
+def flowcache_uniform_decide(x_cur: torch.Tensor, x_prev: torch.Tensor, step_idx: torch.Tensor,
+                             warmup_m: int, eps: float, acc_global: torch.Tensor,
+                             x_compact: Optional[torch.Tensor] = None, gather: bool = True,
+                             workspace: Optional[torch.Tensor] = None, stream=None
+                             ) -> Dict[str, torch.Tensor]:
+    """Uniform policy: acc_global (float64 ``[1]``) is the one shared accumulator, updated in place."""
+    A = x_cur.shape[0]
+    chunk_elems = x_cur[0].numel()
+    dev = x_cur.device
+    assert x_cur.is_contiguous() and x_prev.is_contiguous() and x_prev.shape == x_cur.shape
+    assert acc_global.dtype == torch.float64 and acc_global.numel() == 1 and step_idx.dtype == torch.int32
+    l1rel = torch.empty(1, dtype=torch.float64, device=dev)
+    mask = torch.empty(A, dtype=torch.uint8, device=dev)
+    idx = torch.empty(A, dtype=torch.int32, device=dev)
+    n_rec = torch.empty(1, dtype=torch.int32, device=dev)
+    if x_compact is None and gather:
+        x_compact = torch.empty_like(x_cur)
+    L = lib()
+    if workspace is None:
+        workspace = _workspace(L.flowcache_chunk_decide_workspace(A, chunk_elems), dev)
+    st = L.flowcache_uniform_decide(_ptr(x_cur), _ptr(x_prev), _dtype_code(x_cur), A, chunk_elems,
+                                    _ptr(step_idx), int(warmup_m), float(eps), _ptr(acc_global),
+                                    _ptr(l1rel), _ptr(mask), _ptr(idx), _ptr(n_rec), _ptr(x_compact),
+                                    _ptr(workspace), workspace.numel(), _stream(stream))
+    _check("flowcache_uniform_decide", st)
+    return {"recompute_mask": mask, "recompute_idx": idx, "n_recompute": n_rec, "l1rel": l1rel,
+            "acc": acc_global, "x_compact": x_compact}
+
+
+def flowcache_residual_apply(x_cur: torch.Tensor, y_compact: Optional[torch.Tensor],
+                             residual: torch.Tensor, recompute_idx: torch.Tensor,
+                             n_recompute: torch.Tensor, out: Optional[torch.Tensor] = None,
+                             stream=None) -> torch.Tensor:
+    """x_cur/residual/out ``[A, chunk_elems]``; y_compact the stack's output for the recompute
+    chunks, compact.  Updates ``residual`` in place and returns ``out`` (full layout)."""
+    A = x_cur.shape[0]
+    chunk_elems = x_cur[0].numel()
+    assert x_cur.is_contiguous() and residual.is_contiguous() and residual.shape == x_cur.shape
+    assert residual.dtype == x_cur.dtype and (y_compact is None or y_compact.is_contiguous())
+    if out is None:
+        out = torch.empty_like(x_cur)
+    st = lib().flowcache_residual_apply(_ptr(x_cur), _ptr(y_compact), _ptr(residual), _ptr(out),
+                                        _dtype_code(x_cur), A, chunk_elems, _ptr(recompute_idx),
+                                        _ptr(n_recompute), _stream(stream))
+    _check("flowcache_residual_apply", st)
+    return out
 
 
 def flowcache_attend(q: torch.Tensor, k_new: Optional[torch.Tensor], v_new: Optional[torch.Tensor],

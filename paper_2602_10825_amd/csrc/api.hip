@@ -65,8 +65,39 @@ int flowcache_chunk_decide(const void* x_cur, const void* x_prev, fc_dtype dtype
     if (workspace_bytes < flowcache_chunk_decide_workspace(A, chunk_elems))
         return FC_WORKSPACE_TOO_SMALL;
     FcDecideArgs a{x_cur, x_prev, dtype, A, chunk_elems, step_idx, warmup_m, eps, acc, l1rel,
-                   recompute_mask, recompute_idx, n_recompute, x_compact, workspace};
+                   recompute_mask, recompute_idx, n_recompute, x_compact, workspace, 0};
     return fc_launch_decide(a, (hipStream_t)stream);
+}
+
+int flowcache_uniform_decide(const void* x_cur, const void* x_prev, fc_dtype dtype, int A,
+                             int64_t chunk_elems, const int32_t* step_idx, int warmup_m,
+                             double eps, double* acc_global, double* l1rel,
+                             uint8_t* recompute_mask, int32_t* recompute_idx,
+                             int32_t* n_recompute, void* x_compact, void* workspace,
+                             size_t workspace_bytes, fc_stream stream) {
+    if (!x_cur || !x_prev || !step_idx || !acc_global || !recompute_mask || !recompute_idx ||
+        !n_recompute || !workspace)
+        return FC_INVALID_ARGUMENT;
+    if (bad_dtype(dtype) || A < 1 || A > FC_MAX_ACTIVE || chunk_elems < 1 || warmup_m < 0)
+        return FC_INVALID_ARGUMENT;
+    if (!(eps >= 0.0) || !std::isfinite(eps)) return FC_INVALID_ARGUMENT;
+    if (workspace_bytes < flowcache_chunk_decide_workspace(A, chunk_elems))
+        return FC_WORKSPACE_TOO_SMALL;
+    FcDecideArgs a{x_cur, x_prev, dtype, A, chunk_elems, step_idx, warmup_m, eps, acc_global,
+                   l1rel, recompute_mask, recompute_idx, n_recompute, x_compact, workspace, 1};
+    return fc_launch_decide(a, (hipStream_t)stream);
+}
+
+int flowcache_residual_apply(const void* x_cur, const void* y_compact, void* residual, void* out,
+                             fc_dtype dtype, int A, int64_t chunk_elems,
+                             const int32_t* recompute_idx, const int32_t* n_recompute,
+                             fc_stream stream) {
+    if (!x_cur || !residual || !out || !recompute_idx || !n_recompute) return FC_INVALID_ARGUMENT;
+    if (bad_dtype(dtype) || A < 1 || A > FC_MAX_ACTIVE || chunk_elems < 1)
+        return FC_INVALID_ARGUMENT;
+    FcResidualArgs a{x_cur, y_compact, residual, out, dtype, A, chunk_elems, recompute_idx,
+                     n_recompute};
+    return fc_launch_residual(a, (hipStream_t)stream);
 }
 
 // ------------------------------------------------------------------ attention mass

@@ -1,4 +1,5 @@
-// Change metric, reuse decision and gather (Sec. 3.2, Eq. (5) and Eq. (8)).
+// Change metric, reuse decision and gather (Sec. 3.2, Eq. (5) and Eq. (8)); also the uniform
+// policy of Fig. 2 (top) as a mode of the decision kernel.
 //
 // Three stream-ordered kernels:
 //   1. decide_reduce   streaming pass over x_cur / x_prev: per block partial sums of
@@ -104,7 +105,8 @@ __global__ __launch_bounds__(kThreads) void decide_reduce_kernel(
 __global__ __launch_bounds__(kThreads) void decide_finalize_kernel(
     const double* __restrict__ partial, int A, int bpc, const int32_t* __restrict__ step_idx,
     int warmup_m, double eps, double* __restrict__ acc, double* __restrict__ l1rel,
-    uint8_t* __restrict__ mask, int32_t* __restrict__ idx, int32_t* __restrict__ n_rec) {
+    uint8_t* __restrict__ mask, int32_t* __restrict__ idx, int32_t* __restrict__ n_rec,
+    int uniform) {
     __shared__ double sh[2][kThreads];
     __shared__ double tot[2][FC_MAX_ACTIVE];
     const int tid = threadIdx.x;
@@ -124,7 +126,30 @@ __global__ __launch_bounds__(kThreads) void decide_finalize_kernel(
         if (tid == 0) { tot[0][i] = sh[0][0]; tot[1][i] = sh[1][0]; }
         __syncthreads();
     }
-    if (tid == 0) {
+    if (tid == 0 && uniform) {
+        // Fig. 2, top: the chunks past warm-up share one metric, accumulator and decision
+        double num = 0.0, den = 0.0;
+        int old = 0;
+        for (int i = 0; i < A; ++i)
+            if (step_idx[i] >= warmup_m) { num += tot[0][i]; den += tot[1][i]; ++old; }
+        double f = 0.0;
+        double rel = __longlong_as_double(0x7ff8000000000000LL);   // NaN: no chunk to measure
+        if (old) {
+            rel = (den == 0.0) ? __longlong_as_double(0x7ff0000000000000LL) : num / den;
+            const double a = acc[0] + rel;
+            f = (a > eps) ? 0.0 : a;
+        }
+        acc[0] = f;
+        if (l1rel) l1rel[0] = rel;
+        int cnt = 0;
+        for (int i = 0; i < A; ++i) {
+            const bool rec = (step_idx[i] < warmup_m) || (f == 0.0);
+            mask[i] = rec ? 1 : 0;
+            if (rec) idx[cnt++] = i;
+        }
+        for (int i = cnt; i < A; ++i) idx[i] = -1;
+        *n_rec = cnt;
+    } else if (tid == 0) {
         int cnt = 0;
         for (int i = 0; i < A; ++i) {
             const double num = tot[0][i], den = tot[1][i];
@@ -188,7 +213,7 @@ int launch_typed(const FcDecideArgs& a, hipStream_t s) {
             (const T*)a.x_cur, (const T*)a.x_prev, a.chunk_elems, bpc, partial);
     FC_LAUNCH_CHECK();
     decide_finalize_kernel<<<1, kThreads, 0, s>>>(partial, a.A, bpc, a.step_idx, a.warmup_m,
-                                                  a.eps, a.acc, a.l1rel, a.mask, a.idx, a.n_rec);
+                                                  a.eps, a.acc, a.l1rel, a.mask, a.idx, a.n_rec, a.uniform);
     FC_LAUNCH_CHECK();
     if (a.x_compact) {
         const bool cvec = vec && ((uintptr_t)a.x_compact % 16 == 0);

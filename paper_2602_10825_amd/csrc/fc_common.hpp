@@ -91,9 +91,16 @@ struct FcDecideArgs {
     const void* x_cur; const void* x_prev; fc_dtype dtype; int A; int64_t chunk_elems;
     const int32_t* step_idx; int warmup_m; double eps; double* acc; double* l1rel;
     uint8_t* mask; int32_t* idx; int32_t* n_rec; void* x_compact; void* ws;
+    int uniform;   // 1: one shared accumulator acc[0] / l1rel[0] for all chunks past warm-up
 };
 int fc_decide_blocks_per_chunk(int A, int64_t chunk_elems, fc_dtype dtype);
 int fc_launch_decide(const FcDecideArgs& a, hipStream_t s);
+
+struct FcResidualArgs {
+    const void* x_cur; const void* y_compact; void* residual; void* out; fc_dtype dtype;
+    int A; int64_t chunk_elems; const int32_t* idx; const int32_t* n_rec;
+};
+int fc_launch_residual(const FcResidualArgs& a, hipStream_t s);
 
 struct FcAttendArgs {
     const void* q; void* out; float* lse;
