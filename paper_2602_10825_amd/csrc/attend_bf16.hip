@@ -33,6 +33,7 @@ namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
@@ -60,19 +61,27 @@ struct TileIter {
     bool done;
 };
 
+// Tile -> registers.  The tile's first row is a wavefront-uniform base; each lane adds a 32-bit
+// byte offset (precomputed for full tiles, clamped to the last valid row for a ragged one).
 template <int LD, int ROWS_PER_PASS>
 __device__ __forceinline__ void prefetch_tile(u32x4_native (&kreg)[LD], u32x4_native (&vreg)[LD],
                                               const bf16_t* kbase, const bf16_t* vbase,
                                               const TileIter& t, int64_t tok_stride, int ld_row,
-                                              int ld_col) {
+                                              int ld_col, const uint32_t (&voff_full)[LD]) {
     const int nvalid = (t.len - t.t0 < BK) ? t.len - t.t0 : BK;
+    const int64_t tile_off = (int64_t)(t.start + t.t0) * tok_stride;
+    const char* kt = reinterpret_cast<const char*>(kbase + tile_off);
+    const char* vt = reinterpret_cast<const char*>(vbase + tile_off);
 #pragma unroll
     for (int p = 0; p < LD; ++p) {
-        int row = p * ROWS_PER_PASS + ld_row;
-        if (row > nvalid - 1) row = nvalid - 1;
-        const int64_t off = (int64_t)(t.start + t.t0 + row) * tok_stride + ld_col * 8;
-        kreg[p] = *reinterpret_cast<const u32x4_native*>(kbase + off);
-        vreg[p] = *reinterpret_cast<const u32x4_native*>(vbase + off);
+        uint32_t voff = voff_full[p];
+        if (nvalid < BK) {
+            int row = p * ROWS_PER_PASS + ld_row;
+            if (row > nvalid - 1) row = nvalid - 1;
+            voff = ((uint32_t)row * (uint32_t)tok_stride + (uint32_t)ld_col * 8u) * 2u;
+        }
+        kreg[p] = *reinterpret_cast<const u32x4_native*>(kt + voff);
+        vreg[p] = *reinterpret_cast<const u32x4_native*>(vt + voff);
     }
 }
 
@@ -153,26 +162,40 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
     const bf16_t* kbase = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
     const bf16_t* vbase = (const bf16_t*)a.v_cache + (int64_t)hk * a.head_stride;
 
-    // ---- iterator over 64-key tiles of the visible, merged segments
-    TileIter it;
-    auto next_segment = [&](TileIter& t) {
-        while (t.sgi <= c) {
-            int start = (t.sgi < 0) ? 0 : a.active_off[t.sgi];
-            int len = (t.sgi < 0) ? a.L_clean : a.L_c;
-            ++t.sgi;
-            while (t.sgi <= c && a.active_off[t.sgi] == start + len) { len += a.L_c; ++t.sgi; }
-            if (len > 0) { t.start = start; t.len = len; t.t0 = 0; return; }
+    // ---- visible key segments (clean region, then active chunks 0..c; adjacent ones merged),
+    //      listed once so that stepping to the next 64-key tile is branch-free in the main loop
+    __shared__ int seg_start[FC_MAX_ACTIVE + 2], seg_len[FC_MAX_ACTIVE + 2];
+    __shared__ int seg_count;
+    if (tid == 0) {
+        int n = 0, sgi = -1;
+        while (sgi <= c) {
+            int start = (sgi < 0) ? 0 : a.active_off[sgi];
+            int len = (sgi < 0) ? a.L_clean : a.L_c;
+            ++sgi;
+            while (sgi <= c && a.active_off[sgi] == start + len) { len += a.L_c; ++sgi; }
+            if (len > 0) { seg_start[n] = start; seg_len[n] = len; ++n; }
         }
-        t.done = true;
-        t.t0 = 0;   // start/len still describe the last segment: a valid address range
-    };
-    it.sgi = -1; it.start = 0; it.len = 0; it.t0 = 0; it.done = false;
-    next_segment(it);
+        seg_start[n] = seg_start[n - 1];   // sentinel: a valid range for the fetch past the end
+        seg_len[n] = seg_len[n - 1];
+        seg_count = n;
+    }
+    __syncthreads();
+    const int nseg = __builtin_amdgcn_readfirstlane(seg_count);
+    TileIter it;
+    it.sgi = 0;
+    it.start = __builtin_amdgcn_readfirstlane(seg_start[0]);
+    it.len = __builtin_amdgcn_readfirstlane(seg_len[0]);
+    it.t0 = 0;
+    it.done = false;
 
     // Global -> register prefetch of one tile (rows past the end of a segment are clamped
     // to its last row) and its later store to LDS.
     u32x4_native kreg[LD], vreg[LD];
     const int ld_row = tid / VPR, ld_col = tid % VPR;
+    uint32_t voff_full[LD];
+#pragma unroll
+    for (int p = 0; p < LD; ++p)
+        voff_full[p] = ((uint32_t)(p * (NT / VPR) + ld_row) * (uint32_t)a.tok_stride + (uint32_t)ld_col * 8u) * 2u;
     // per-lane offsets of the fragment reads
     const int k_frag_off = l32 * KROW + 8 * hh;
     // transposing V read: lane s of a 16-lane group addresses key (s/4), dv 4*(s%4) of the
@@ -232,15 +255,23 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
 #define FC_EXP(PF, PS)                                                                        \
     _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                        \
         const float mneg = -m[qb];                                                            \
+        const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};                                   \
         float ps0 = 0.f, ps1 = 0.f;                                                           \
         _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                      \
-            _Pragma("unroll") for (int i = 0; i < 16; i += 2) {                               \
+            _Pragma("unroll") for (int i = 0; i < 16; i += 4) {                               \
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i], c2, mneg));     \
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 1], c2, mneg)); \
-                ps0 += p0;                                                                    \
-                ps1 += p1;                                                                    \
-                PF[qb][kb * 2 + (i >> 3)][i & 7] = (__bf16)p0;                                \
-                PF[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = (__bf16)p1;                          \
+                const float p2 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 2], c2, mneg)); \
+                const float p3 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 3], c2, mneg)); \
+                const bf16x2_t lo = {(__bf16)p0, (__bf16)p1};                                 \
+                const bf16x2_t hi = {(__bf16)p2, (__bf16)p3};                                 \
+                /* the sums run over the ROUNDED weights, the ones V is multiplied with */     \
+                ps0 = __builtin_amdgcn_fdot2_f32_bf16(lo, ones, ps0, false);                  \
+                ps1 = __builtin_amdgcn_fdot2_f32_bf16(hi, ones, ps1, false);                  \
+                PF[qb][kb * 2 + (i >> 3)][i & 7] = lo[0];                                     \
+                PF[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = lo[1];                               \
+                PF[qb][kb * 2 + (i >> 3)][(i & 7) + 2] = hi[0];                               \
+                PF[qb][kb * 2 + (i >> 3)][(i & 7) + 3] = hi[1];                               \
             }                                                                                 \
         PS[qb] = ps0 + ps1;                                                                   \
     }
@@ -249,10 +280,16 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
     {                                                                                         \
         pending = !it.done;                                                                   \
         nv_pending = (it.len - it.t0 < BK) ? it.len - it.t0 : BK;                             \
-        prefetch_tile<LD, NT / VPR>(kreg, vreg, kbase, vbase, it, a.tok_stride, ld_row, ld_col); \
-        if (pending) {                                                                        \
-            it.t0 += BK;                                                                      \
-            if (it.t0 >= it.len) next_segment(it);                                            \
+        prefetch_tile<LD, NT / VPR>(kreg, vreg, kbase, vbase, it, a.tok_stride, ld_row, ld_col, \
+                                    voff_full);                                               \
+        {                                                                                     \
+            const bool last = it.t0 + BK >= it.len;          /* leaving this segment */       \
+            const int nsg = (pending && last) ? it.sgi + 1 : it.sgi;                          \
+            it.t0 = (!pending || last) ? 0 : it.t0 + BK;                                      \
+            it.sgi = nsg;                                                                     \
+            it.start = __builtin_amdgcn_readfirstlane(seg_start[nsg]);                        \
+            it.len = __builtin_amdgcn_readfirstlane(seg_len[nsg]);                            \
+            it.done = nsg >= nseg;                                                            \
         }                                                                                     \
     }
 
