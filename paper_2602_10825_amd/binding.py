@@ -28,6 +28,8 @@ EXPORTS = (
     "flowcache_attend", "flowcache_attend_workspace", "flowcache_scatter_kv",
     "flowcache_attention_mass", "flowcache_attention_mass_workspace",
     "flowcache_kv_compress", "flowcache_kv_compress_workspace",
+    "flowcache_sched_state_bytes", "flowcache_sched_init", "flowcache_sched_capacity",
+    "flowcache_sched_total_ticks", "flowcache_sched_next",
 )
 
 _lib = None
@@ -83,6 +85,16 @@ def lib() -> ctypes.CDLL:
     L.flowcache_kv_compress.restype = c_int
     L.flowcache_kv_compress.argtypes = [c_vp, c_vp, c_i64, c_i64, c_int, c_int, c_int, c_int, c_int,
                                         c_vp, c_int, c_d, c_vp, c_vp, c_sz, c_vp]
+    L.flowcache_sched_state_bytes.restype = c_sz
+    L.flowcache_sched_state_bytes.argtypes = []
+    L.flowcache_sched_init.restype = c_int
+    L.flowcache_sched_init.argtypes = [c_vp, c_sz, c_vp]
+    L.flowcache_sched_capacity.restype = c_i64
+    L.flowcache_sched_capacity.argtypes = [c_vp]
+    L.flowcache_sched_total_ticks.restype = c_i64
+    L.flowcache_sched_total_ticks.argtypes = [c_vp]
+    L.flowcache_sched_next.restype = c_int
+    L.flowcache_sched_next.argtypes = [c_vp, c_vp]
     _lib = L
     return L
 
@@ -291,6 +303,59 @@ def flowcache_kv_compress(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int
 
 
 # --------------------------------------------------------------------------------------
+# ---- host-side tick scheduler (flowcache_sched.h) ------------------------------------------
+FC_MAX_ACTIVE = 16
+FC_SCHED_DONE = 5
+
+
+class SchedConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_units", "steps", "stagger", "window", "L_c", "budget", "prefix_tokens")]
+
+
+class Tick(ctypes.Structure):
+    _fields_ = [("tick", ctypes.c_int32), ("A", ctypes.c_int32),
+                ("unit", ctypes.c_int32 * FC_MAX_ACTIVE), ("step_idx", ctypes.c_int32 * FC_MAX_ACTIVE),
+                ("active_off", ctypes.c_int32 * FC_MAX_ACTIVE), ("L_clean", ctypes.c_int32),
+                ("commit_unit", ctypes.c_int32), ("commit_src_off", ctypes.c_int32),
+                ("commit_dst_off", ctypes.c_int32), ("merged_len", ctypes.c_int32),
+                ("compress", ctypes.c_int32), ("L_clean_after", ctypes.c_int32)]
+
+    def as_dict(self) -> Dict[str, object]:
+        A = self.A
+        return {"tick": self.tick, "A": A, "unit": list(self.unit[:A]), "step_idx": list(self.step_idx[:A]),
+                "active_off": list(self.active_off[:A]), "L_clean": self.L_clean,
+                "commit_unit": self.commit_unit, "commit_src_off": self.commit_src_off,
+                "commit_dst_off": self.commit_dst_off, "merged_len": self.merged_len,
+                "compress": self.compress, "L_clean_after": self.L_clean_after}
+
+
+class Scheduler:
+    """Iterator over the ticks of a chunk-autoregressive denoising schedule (argument
+    marshalling only: the state machine lives in the library)."""
+
+    def __init__(self, n_units: int, steps: int, stagger: int, L_c: int, budget: int,
+                 window: int = 0, prefix_tokens: int = 0):
+        L = lib()
+        self._cfg = SchedConfig(n_units, steps, stagger, window, L_c, budget, prefix_tokens)
+        self._state = ctypes.create_string_buffer(L.flowcache_sched_state_bytes())
+        _check("flowcache_sched_init",
+               L.flowcache_sched_init(self._state, len(self._state), ctypes.byref(self._cfg)))
+        self.capacity = int(L.flowcache_sched_capacity(self._state))
+        self.total_ticks = int(L.flowcache_sched_total_ticks(self._state))
+
+    def __iter__(self):
+        return self
+
+    def __next__(self) -> Dict[str, object]:
+        t = Tick()
+        st = lib().flowcache_sched_next(self._state, ctypes.byref(t))
+        if st == FC_SCHED_DONE:
+            raise StopIteration
+        _check("flowcache_sched_next", st)
+        return t.as_dict()
+
+
 def to_device(arr, dtype: str, device="cuda") -> torch.Tensor:
     """numpy storage array (float32, or uint16 bfloat16 bit patterns) -> device tensor."""
     import numpy as np

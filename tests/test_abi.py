@@ -9,7 +9,8 @@ import pytest
 from paper_2602_10825_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "flowcache.h")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))
+                 if f.endswith(".h"))
 
 INVALID, UNSUPPORTED, WS_SMALL = 1, 2, 3
 P = ctypes.c_void_p(0x10000)       # never dereferenced: validation fails first
@@ -25,7 +26,7 @@ def L():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "\n".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(flowcache_\w+)\s*\(", text)))
 
