@@ -102,6 +102,51 @@ def cpu_baseline(wl, d, a, rows_per_chunk):
     }
 
 
+def widened_rows(wl, B, x_cur, x_prev, x_compact, step_idx, dec, q, k_cache, ws_dec, L_k, reps=5):
+    """Calls outside the timed step (rows widened into after the hot path): timed alone, HIP
+    events, operands rotated like the step's."""
+    import torch
+    esz = 2 if wl.dtype == "bf16" else 4
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def best(fn):
+        ts = []
+        for i in range(reps + 1):
+            e0.record(); fn(i); e1.record(); e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.mean(ts[1:]))
+
+    one = wl.A * wl.chunk_elems * esz
+    res = torch.zeros_like(x_cur[0])
+    out = torch.empty_like(x_cur[0])
+    none = torch.full((wl.A,), -1, dtype=torch.int32, device=q.device)
+    zero = torch.zeros(1, dtype=torch.int32, device=q.device)
+    accg = torch.zeros(1, dtype=torch.float64, device=q.device)
+    rows = []
+    ms = best(lambda i: B.flowcache_residual_apply(x_cur[i % len(x_cur)], x_compact, res,
+                                                   dec["recompute_idx"], dec["n_recompute"], out=out))
+    rows.append({"call": "residual_apply (all chunks recomputed: store)", "ms": ms,
+                 "algorithmic_bytes": 4 * one, "GBps": 4 * one / ms / 1e6})
+    ms = best(lambda i: B.flowcache_residual_apply(x_cur[i % len(x_cur)], None, res, none, zero, out=out))
+    rows.append({"call": "residual_apply (all chunks reused: apply)", "ms": ms,
+                 "algorithmic_bytes": 3 * one, "GBps": 3 * one / ms / 1e6})
+    ms = best(lambda i: B.flowcache_uniform_decide(x_cur[i % len(x_cur)], x_prev[i % len(x_prev)], step_idx,
+                                                   wl.warmup_m, 0.0, accg, x_compact=x_compact,
+                                                   workspace=ws_dec))
+    rows.append({"call": "uniform_decide (+ gather)", "ms": ms, "algorithmic_bytes": 4 * one,
+                 "GBps": 4 * one / ms / 1e6})
+    Wf = wl.L_c // 5                         # frame-level observation queries: one fifth of a chunk
+    q_frame = q[wl.A * wl.L_c - Wf:]
+    ms = best(lambda i: B.flowcache_attention_mass(q_frame, k_cache, L_k))
+    fl = 2.0 * 2 * wl.d * Wf * wl.H_q * L_k                # two passes of Q K^T
+    rows.append({"call": f"attention_mass, frame-level queries (W = {Wf})", "ms": ms,
+                 "algorithmic_flops": fl, "TFLOPps": fl / ms / 1e9})
+    for r in rows:
+        if "GBps" in r:
+            r["frac_of_hbm_peak"] = r["GBps"] / PEAK_HBM_GBPS
+    return rows
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -226,6 +271,8 @@ def main():
                   hbm("compress", cmp_bytes)],
         "stage_ms": stage_ms,
     }
+    result["widened_rows"] = widened_rows(wl, B, x_cur, x_prev, x_compact, step_idx, dec, q, k_sets[0],
+                                          ws_dec, L_k)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, d, a, args.cpu_rows)
     else:
