@@ -1,30 +1,35 @@
 // bf16 chunk-causal flash attention on the CDNA4 matrix cores (Sec. 3.3:
 // softmax(q K^T d^-1/2) V, clean KV cache + active chunks 0..c visible to chunk c).
 //
-// One workgroup = 256 query rows of one head of one recompute chunk, 4 wavefronts of
-// 64 rows each.  Per 64-key tile:
+// One workgroup = 256 query rows of one head of one recompute chunk: 8 wavefronts of 32 rows,
+// two per SIMD with 256 registers each (a single wavefront per SIMD cannot issue fast enough:
+// one instruction per four cycles, and the matrix, vector and LDS streams of this loop add up
+// to about 290 instructions per tile).  Per 64-key tile:
 //   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K fragment from LDS, B = Q fragment held
 //                 in registers.  Computing the transpose puts one query per lane
 //                 (column = lane % 32) and 16 keys of each 32-key block in that lane's
 //                 accumulator registers, so the row max / row sum are in-lane reductions
 //                 plus one exchange with lane ^ 32.
-//   P   = exp2(S^T * scale*log2(e) - m)  fp32, online max / sum, cast to bf16 in place:
-//                 the accumulator layout already is the B-operand layout of the next
-//                 product (contraction index = key, with a fixed permutation of the keys
-//                 inside each 16-key group that V's LDS layout mirrors).
+//   P   = exp2(S^T * scale*log2(e) - m)  fp32, cast to bf16 in place: the accumulator
+//                 layout already is the B-operand layout of the next product (contraction
+//                 index = key, with a fixed permutation of the keys inside each 16-key
+//                 group that V's LDS layout mirrors).  The row sums are taken over the
+//                 ROUNDED weights (v_dot2c_f32_bf16 with a vector of ones), i.e. over
+//                 exactly the weights V is multiplied with.
 //   O^T += V^T P^T  A = V^T fragment read from the row-major V tile with the transposing
 //                 LDS load ds_read_b64_tr_b16 (each 16-lane group turns 4 keys x 16 dv into
 //                 16 lanes x 4 keys), two loads per 8-key fragment.
 // The reference point m of the exponent is NOT the running row max: it is raised (and O, l
-// rescaled) only when some P of a tile exceeds 2^40, which the row sums reveal for free.
+// rescaled) only when some row sum of a tile exceeds 2^40, which the sums reveal for free.
 // exp2(S c2 - m) then stays far inside the fp32 / bf16 exponent range, the final O / l is
 // unchanged, and the steady state carries no row-max reduction and no rescale at all.
 // The first tile always takes the raise path once (m starts at -1e30).
 // O += V P of tile j-1 is issued together with the exp2 / sum / pack of tile j, so the
-// matrix cores work while the vector ALU turns S into P (one wavefront per SIMD: nothing
-// else hides the vector work).  K/V tiles are fetched with 16-byte global loads one tile
-// ahead and live in a ring of three LDS buffers (tile j-1 still feeds O += V P while tile
-// j+1 is being written): one barrier per tile.
+// matrix cores work while the vector ALU turns S into P.  K/V tiles are fetched with 16-byte
+// global loads one tile ahead (wavefront-uniform tile base + 32-bit lane offset) and live in a
+// ring of three LDS buffers (tile j-1 still feeds O += V P while tile j+1 is being written):
+// one barrier per tile.  The visible key segments are listed once per workgroup in LDS, so
+// stepping to the next tile is branch-free.
 // Work-groups are mapped so that the 32 compute units of one XCD work on the same head
 // and chunk at the same time and share the K/V stream through that XCD's L2.
 #include "fc_common.hpp"
