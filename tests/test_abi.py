@@ -151,3 +151,26 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(ImportError):
         binding.lib()
+
+
+def test_uniform_decide_and_residual_apply_reject_bad_arguments(L):
+    def uni(**kw):
+        a = dict(x_cur=P, x_prev=P, dtype=1, A=2, chunk_elems=1024, step_idx=P, m=4, eps=0.1, acc=P,
+                 l1rel=P, mask=P, idx=P, n=P, xc=P, ws=P, wsb=1 << 20, stream=NULL)
+        a.update(kw)
+        return L.flowcache_uniform_decide(a["x_cur"], a["x_prev"], a["dtype"], a["A"], a["chunk_elems"],
+                                          a["step_idx"], a["m"], a["eps"], a["acc"], a["l1rel"], a["mask"],
+                                          a["idx"], a["n"], a["xc"], a["ws"], a["wsb"], a["stream"])
+
+    assert uni(acc=NULL) == INVALID and uni(A=0) == INVALID and uni(eps=-1.0) == INVALID
+    assert uni(eps=float("nan")) == INVALID and uni(dtype=5) == INVALID and uni(wsb=8) == WS_SMALL
+
+    def res(**kw):
+        a = dict(x=P, y=P, r=P, o=P, dtype=1, A=2, ce=1024, idx=P, n=P, stream=NULL)
+        a.update(kw)
+        return L.flowcache_residual_apply(a["x"], a["y"], a["r"], a["o"], a["dtype"], a["A"], a["ce"],
+                                          a["idx"], a["n"], a["stream"])
+
+    assert res(x=NULL) == INVALID and res(r=NULL) == INVALID and res(o=NULL) == INVALID
+    assert res(idx=NULL) == INVALID and res(n=NULL) == INVALID
+    assert res(A=0) == INVALID and res(A=17) == INVALID and res(ce=0) == INVALID and res(dtype=2) == INVALID

@@ -194,6 +194,27 @@ def test_attend_no_clean_context_and_nothing_to_recompute():
     assert got.shape[0] == 0
 
 
+def test_attend_bf16_when_later_keys_dwarf_earlier_ones():
+    """Key magnitudes grow along the cache, so the scores of later tiles exceed the exponent
+    reference of the earlier ones by far more than 2^40: the kernel has to raise its reference
+    (rescale its running output and row sums) several times, in the clean region and again in
+    the active chunks."""
+    wl = synth.MID_BF16
+    a = synth.attend_inputs(wl, seed=6)
+    ramp = np.linspace(0.05, 30.0, wl.capacity)[None, :, None]
+    a["k_cache"] = synth.to_storage((O.widen(a["k_cache"]) * ramp).astype(np.float32), "bf16")
+    kn = O.widen(a["k_new"]).reshape(wl.A, wl.L_c, wl.H_k, wl.d)
+    grow = np.linspace(20.0, 60.0, wl.A * wl.L_c).reshape(wl.A, wl.L_c, 1, 1)
+    a["k_new"] = synth.to_storage((kn * grow).astype(np.float32).reshape(-1, wl.H_k, wl.d), "bf16")
+    got, ref, res, ref_lse, _, _ = run_attend(wl, a, [0, 1, 2])
+    err = np.abs(got - ref)
+    # outputs are O(1) here (a few keys dominate each row): relative bars
+    assert np.sqrt((err ** 2).sum()) / np.sqrt((ref ** 2).sum()) <= 1e-2
+    assert err.max() <= 2e-2 * max(1.0, np.abs(ref).max())
+    lse = res["lse"].cpu().numpy()[:, :3 * wl.L_c]
+    assert np.abs(lse - ref_lse).max() <= 2e-2 * np.abs(ref_lse).max()
+
+
 # ------------------------------------------------------------------ importance mass
 @pytest.mark.parametrize("wl,W", [(synth.C1, 50), (synth.C1_MHA, 50), (synth.MID_BF16, 50),
                                   (synth.MID_BF16_GQA, 0), (synth.MID_F32, 100)])
