@@ -21,6 +21,7 @@
  *                             scatter half of the gather step; Sec. 3.2).
  *   flowcache_attention_mass  the importance mass alone, for explicit observation queries
  *                             (Sec. 3.3, Eq. (9); observation window of App. C.2).
+ *   flowcache_kv_compress_grouped  the same at frame / chunk key granularity (App. D.2.1).
  *   flowcache_kv_compress     joint importance-redundancy scoring, per-head top-B selection
  *                             and in-place compaction of K and V (Sec. 3.3, Eq. (10)-(12),
  *                             linear-time redundancy of App. C.2, phases of App. C.1).
@@ -251,6 +252,29 @@ int flowcache_kv_compress(void* k_cache, void* v_cache, int64_t kv_head_stride,
                           int32_t* kept_idx, void* workspace, size_t workspace_bytes,
                           fc_stream stream);
 size_t flowcache_kv_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype);
+
+/*
+ * The same compression with keys scored and kept at a coarser granularity (the frame- and
+ * chunk-level key granularities of the ablation in App. D.2.1).  The first L_k positions
+ * are split into groups of `group` consecutive tokens (a latent frame, or a chunk).  A group
+ * is represented by the mean of its keys and the mean of its tokens' mass (float64 sums,
+ * rounded once to float32); Eq. (10)-(12) and the top-B selection run over the groups exactly
+ * as they run over tokens in flowcache_kv_compress; every token of a kept group is kept.
+ *
+ *   group    tokens per group, >= 1 (1 = flowcache_kv_compress); L_k and budget (both in
+ *            tokens) must be multiples of it
+ *   pool_k   window of Eq. (10), counted in groups
+ *   kept_idx [dev] [H_k, min(budget, L_k)] int32 out: kept TOKEN positions, ascending
+ * Errors as for flowcache_kv_compress, plus FC_INVALID_ARGUMENT when L_k or budget is not a
+ * multiple of group.
+ */
+int flowcache_kv_compress_grouped(void* k_cache, void* v_cache, int64_t kv_head_stride,
+                                  int64_t kv_tok_stride, fc_dtype dtype, int H_k, int d, int L_k,
+                                  int budget, int group, const float* mass, int pool_k,
+                                  double lambda, int32_t* kept_idx, void* workspace,
+                                  size_t workspace_bytes, fc_stream stream);
+size_t flowcache_kv_compress_grouped_workspace(int H_k, int L_k, int d, int budget, int group,
+                                               fc_dtype dtype);
 
 #ifdef __cplusplus
 }

@@ -21,6 +21,9 @@ special cases) live in ``tests/test_oracle_*.py``.  Pin status:
   redundancy (linear / quadratic) .......... pinned (identity of App. C.2, closed forms)
   select_top_b ............................. pinned (brute-force rank count)
   compact_kv, kv_compress .................. pinned (identity case, exact copies)
+  kv_compress_grouped ...................... pinned (group = 1 is kv_compress; identical tokens
+                                             inside each group reduce it to kv_compress on one
+                                             token per group; hand-worked case)
   Parity unpinned (the paper gives no value): the max-pool kernel size, the exact
   attention mask and the order of the surviving tokens rest on the readings below.
 
@@ -410,3 +413,40 @@ def kv_compress(k_cache: np.ndarray, v_cache: np.ndarray, L_k: int, budget: int,
     if budget >= L_k:
         return kept, k_cache.copy(), v_cache.copy(), scores
     return kept, compact_kv(k_cache, kept), compact_kv(v_cache, kept), scores
+
+
+# ======================================================================================
+# Key granularity above the token -- App. D.2.1 (frame- / chunk-level keys)
+# ======================================================================================
+def kv_compress_grouped(k_cache: np.ndarray, v_cache: np.ndarray, L_k: int, budget: int, group: int,
+                        mass: np.ndarray, pool_k: int = 7, lam: float = 0.07):
+    """Compression with keys scored and kept in groups of ``group`` consecutive tokens.
+
+    The paper names the granularities (token, frame, chunk) without saying how a group of keys
+    is represented.  Reading: the group's key is the mean of its keys, its importance the mean
+    of its tokens' mass, each a float64 mean rounded once to float32; Eq. (10)-(12) and the
+    top-B selection then run over groups exactly as they do over tokens, and all tokens of a
+    kept group are kept.  Returns (kept token indices [H, budget], new K, new V, group scores).
+    """
+    assert L_k % group == 0 and budget % group == 0
+    H = k_cache.shape[0]
+    G, Bg = L_k // group, budget // group
+    k_new, v_new = np.array(k_cache, copy=True), np.array(v_cache, copy=True)
+    if budget >= L_k:
+        kept = np.tile(np.arange(L_k, dtype=np.int32), (H, 1))
+        return kept, k_new, v_new, None
+    kept = np.empty((H, budget), dtype=np.int32)
+    scores = []
+    for h in range(H):
+        kw = widen(k_cache[h, :L_k]).reshape(G, group, -1)
+        kg = (kw.sum(axis=1) / group).astype(np.float32)
+        mg = (np.asarray(mass[h, :L_k], dtype=np.float64).reshape(G, group).sum(axis=1) / group
+              ).astype(np.float32)
+        sc = selection_scores(kg, mg, pool_k, lam)
+        groups = select_top_b(sc, Bg)
+        kept[h] = (np.asarray(groups, dtype=np.int64)[:, None] * group
+                   + np.arange(group)[None, :]).reshape(-1).astype(np.int32)
+        k_new[h, :budget] = k_cache[h, kept[h]]
+        v_new[h, :budget] = v_cache[h, kept[h]]
+        scores.append(sc)
+    return kept, k_new, v_new, scores

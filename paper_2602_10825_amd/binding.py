@@ -28,6 +28,7 @@ EXPORTS = (
     "flowcache_attend", "flowcache_attend_workspace", "flowcache_scatter_kv",
     "flowcache_attention_mass", "flowcache_attention_mass_workspace",
     "flowcache_kv_compress", "flowcache_kv_compress_workspace",
+    "flowcache_kv_compress_grouped", "flowcache_kv_compress_grouped_workspace",
     "flowcache_sched_state_bytes", "flowcache_sched_init", "flowcache_sched_capacity",
     "flowcache_sched_total_ticks", "flowcache_sched_next",
 )
@@ -85,6 +86,11 @@ def lib() -> ctypes.CDLL:
     L.flowcache_kv_compress.restype = c_int
     L.flowcache_kv_compress.argtypes = [c_vp, c_vp, c_i64, c_i64, c_int, c_int, c_int, c_int, c_int,
                                         c_vp, c_int, c_d, c_vp, c_vp, c_sz, c_vp]
+    L.flowcache_kv_compress_grouped_workspace.restype = c_sz
+    L.flowcache_kv_compress_grouped_workspace.argtypes = [c_int] * 6
+    L.flowcache_kv_compress_grouped.restype = c_int
+    L.flowcache_kv_compress_grouped.argtypes = [c_vp, c_vp, c_i64, c_i64, c_int, c_int, c_int, c_int, c_int,
+                                                c_int, c_vp, c_int, c_d, c_vp, c_vp, c_sz, c_vp]
     L.flowcache_sched_state_bytes.restype = c_sz
     L.flowcache_sched_state_bytes.argtypes = []
     L.flowcache_sched_init.restype = c_int
@@ -299,6 +305,31 @@ def flowcache_kv_compress(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int
                                  float(lam), _ptr(kept_idx), _ptr(workspace), workspace.numel(),
                                  _stream(stream))
     _check("flowcache_kv_compress", st)
+    return kept_idx
+
+
+def flowcache_kv_compress_grouped(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int, budget: int,
+                                  group: int, mass: torch.Tensor, pool_k: int = 7, lam: float = 0.07,
+                                  kept_idx: Optional[torch.Tensor] = None,
+                                  workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """As flowcache_kv_compress, with keys scored and kept in groups of ``group`` consecutive
+    tokens (``L_k`` and ``budget`` are token counts, multiples of ``group``)."""
+    H_k, capacity, d = k_cache.shape
+    dev = k_cache.device
+    assert k_cache.stride(2) == 1 and v_cache.stride() == k_cache.stride()
+    assert mass.dtype == torch.float32 and mass.is_contiguous() and mass.shape == (H_k, L_k)
+    assert L_k <= capacity
+    if kept_idx is None:
+        kept_idx = torch.empty((H_k, min(budget, L_k)), dtype=torch.int32, device=dev)
+    L = lib()
+    code = _dtype_code(k_cache)
+    if workspace is None:
+        workspace = _workspace(L.flowcache_kv_compress_grouped_workspace(H_k, L_k, d, budget, group, code), dev)
+    st = L.flowcache_kv_compress_grouped(_ptr(k_cache), _ptr(v_cache), k_cache.stride(0), k_cache.stride(1),
+                                         code, H_k, d, int(L_k), int(budget), int(group), _ptr(mass),
+                                         int(pool_k), float(lam), _ptr(kept_idx), _ptr(workspace),
+                                         workspace.numel(), _stream(stream))
+    _check("flowcache_kv_compress_grouped", st)
     return kept_idx
 
 

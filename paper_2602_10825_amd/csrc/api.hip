@@ -239,6 +239,34 @@ int flowcache_attend(const void* q, const void* k_new, const void* v_new, void* 
 }
 
 // ------------------------------------------------------------------ kv_compress
+size_t flowcache_kv_compress_grouped_workspace(int H_k, int L_k, int d, int budget, int group,
+                                               fc_dtype dtype) {
+    if (H_k < 1 || L_k < 1 || budget < 1 || group < 1 || (d != 64 && d != 128) || bad_dtype(dtype))
+        return 0;
+    if (L_k % group != 0 || budget % group != 0) return 0;
+    if (group == 1) return fc_compress_workspace(H_k, L_k, d, budget, dtype);
+    return fc_compress_grouped_workspace(H_k, L_k, d, budget, group);
+}
+
+int flowcache_kv_compress_grouped(void* k_cache, void* v_cache, int64_t kv_head_stride,
+                                  int64_t kv_tok_stride, fc_dtype dtype, int H_k, int d, int L_k,
+                                  int budget, int group, const float* mass, int pool_k,
+                                  double lambda, int32_t* kept_idx, void* workspace,
+                                  size_t workspace_bytes, fc_stream stream) {
+    if (!mass || !kept_idx || !workspace) return FC_INVALID_ARGUMENT;
+    if (L_k < 1 || budget < 1 || group < 1) return FC_INVALID_ARGUMENT;
+    if (L_k % group != 0 || budget % group != 0) return FC_INVALID_ARGUMENT;
+    if (pool_k < 1 || pool_k % 2 == 0) return FC_INVALID_ARGUMENT;
+    if (!(lambda >= 0.0 && lambda <= 1.0)) return FC_INVALID_ARGUMENT;
+    int st = check_kv_layout(k_cache, v_cache, kv_head_stride, kv_tok_stride, L_k, dtype, H_k, d);
+    if (st != FC_OK) return st;
+    if (workspace_bytes < flowcache_kv_compress_grouped_workspace(H_k, L_k, d, budget, group, dtype))
+        return FC_WORKSPACE_TOO_SMALL;
+    FcCompressArgs c{k_cache, v_cache, kv_head_stride, kv_tok_stride, dtype, H_k, d, L_k, budget,
+                     mass, pool_k, lambda, kept_idx, workspace, group};
+    return fc_launch_compress(c, (hipStream_t)stream);
+}
+
 size_t flowcache_kv_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype) {
     if (H_k < 1 || L_k < 1 || budget < 1 || (d != 64 && d != 128) || bad_dtype(dtype)) return 0;
     return fc_compress_workspace(H_k, L_k, d, budget, dtype);
@@ -258,7 +286,7 @@ int flowcache_kv_compress(void* k_cache, void* v_cache, int64_t kv_head_stride,
     if (workspace_bytes < fc_compress_workspace(H_k, L_k, d, budget, dtype))
         return FC_WORKSPACE_TOO_SMALL;
     FcCompressArgs c{k_cache, v_cache, kv_head_stride, kv_tok_stride, dtype, H_k, d, L_k, budget,
-                     mass, pool_k, lambda, kept_idx, workspace};
+                     mass, pool_k, lambda, kept_idx, workspace, 1};
     return fc_launch_compress(c, (hipStream_t)stream);
 }
 

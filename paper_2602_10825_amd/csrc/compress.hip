@@ -692,7 +692,7 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
 }
 
 template <typename T, int D>
-int launch_typed(const FcCompressArgs& a, hipStream_t s) {
+int launch_typed(const FcCompressArgs& a, hipStream_t s, bool compact = true) {
     const WsLayout w = layout(a.H_k, a.L_k, a.d, a.budget, a.dtype);
     char* ws = reinterpret_cast<char*>(a.ws);
     double2* tokinfo = reinterpret_cast<double2*>(ws + w.tokinfo);
@@ -724,6 +724,114 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s) {
     FC_LAUNCH_CHECK();
     write_kept_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, sel, a.L_k, a.budget, a.kept);
     FC_LAUNCH_CHECK();
+    if (!compact) return FC_OK;   // scoring and selection only (the grouped variant moves rows itself)
+    constexpr int VPR = D * (int)sizeof(T) / 16;
+    const int64_t hs = a.head_stride * (int64_t)sizeof(T) / 16, ts = a.tok_stride * (int64_t)sizeof(T) / 16;
+    compact_rows_kernel<VPR><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
+        (uint4*)a.k_cache, (uint4*)a.v_cache, hs, ts, a.H_k, a.L_k, a.budget, w.ntile, a.kept, sync);
+    FC_LAUNCH_CHECK();
+    return FC_OK;
+}
+
+// ---- key granularity above the token (frame- or chunk-level keys, App. D.2.1) ------------
+// Group g = tokens [g*group, (g+1)*group): its key is the mean key, its importance the mean
+// mass, both summed in float64 in a fixed order and rounded once to float32.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void group_pool_kernel(
+    const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int group, int G,
+    const float* __restrict__ mass, int L, float* __restrict__ k_pooled,
+    float* __restrict__ mass_pooled) {
+    typedef Slice<T, D> S;
+    constexpr int EL = S::EL;
+    const int g = blockIdx.x, h = blockIdx.y;
+    const int r0 = threadIdx.x / 16, u = threadIdx.x % 16;
+    const T* base = k_cache + (int64_t)h * head_stride + (int64_t)g * group * tok_stride;
+    double acc[EL];
+#pragma unroll
+    for (int e = 0; e < EL; ++e) acc[e] = 0.0;
+    for (int r = r0; r < group; r += kGroups) {
+        double x[EL];
+        S::widen(S::load(base + (int64_t)r * tok_stride, u), x);
+#pragma unroll
+        for (int e = 0; e < EL; ++e) acc[e] += x[e];
+    }
+    __shared__ double sh[kGroups][D];
+    __shared__ double shm[kThreads];
+#pragma unroll
+    for (int e = 0; e < EL; ++e) sh[r0][u * EL + e] = acc[e];
+    double m = 0.0;
+    for (int r = threadIdx.x; r < group; r += kThreads) m += (double)mass[(int64_t)h * L + (int64_t)g * group + r];
+    m = block_sum_fixed<kThreads>(m, shm);   // includes the barrier that publishes sh
+    if (threadIdx.x < D) {
+        double t = 0.0;
+#pragma unroll
+        for (int k = 0; k < kGroups; ++k) t += sh[k][threadIdx.x];
+        k_pooled[((int64_t)h * G + g) * D + threadIdx.x] = (float)(t / (double)group);
+    }
+    if (threadIdx.x == 0) mass_pooled[(int64_t)h * G + g] = (float)(m / (double)group);
+}
+
+// kept groups -> kept token positions; also resets the ticket / flag words the token-level
+// compaction starts from
+__global__ __launch_bounds__(kThreads) void expand_groups_kernel(
+    const int32_t* __restrict__ kept_groups, int n_groups, int group, int32_t* __restrict__ kept,
+    uint32_t* __restrict__ sync, int H, int ntile) {
+    const int h = blockIdx.y;
+    const int64_t n = (int64_t)n_groups * group;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads)
+        kept[(int64_t)h * n + i] = kept_groups[(int64_t)h * n_groups + i / group] * group + (int32_t)(i % group);
+    if (blockIdx.x == 0) {
+        for (int i = threadIdx.x; i < ntile; i += kThreads) sync[64 * (H + 1) + (int64_t)h * ntile + i] = 0u;
+        if (threadIdx.x == 0) sync[64 * (h + 1)] = 0u;
+        if (h == 0 && threadIdx.x == 0) sync[0] = 0u;
+    }
+}
+
+struct GroupedLayout {
+    size_t k_pooled, mass_pooled, kept_groups, inner, sync, total;
+    int G, Bg, ntile;
+};
+
+GroupedLayout grouped_layout(int H, int L, int d, int budget, int group) {
+    GroupedLayout w;
+    w.G = L / group;
+    w.Bg = budget / group;
+    w.ntile = (budget + kTileRows - 1) / kTileRows;
+    size_t off = 0;
+    w.k_pooled = off;    off += fc_align_up((size_t)H * w.G * d * 4);
+    w.mass_pooled = off; off += fc_align_up((size_t)H * w.G * 4);
+    w.kept_groups = off; off += fc_align_up((size_t)H * (w.Bg > 0 ? w.Bg : 1) * 4);
+    w.inner = off;       off += layout(H, w.G, d, w.Bg > 0 ? w.Bg : 1, FC_F32).total;
+    w.sync = off;        off += fc_align_up(((size_t)H * w.ntile + 64 * ((size_t)H + 1)) * 4);
+    w.total = off;
+    return w;
+}
+
+template <typename T, int D>
+int launch_grouped(const FcCompressArgs& a, hipStream_t s) {
+    const GroupedLayout w = grouped_layout(a.H_k, a.L_k, a.d, a.budget, a.group);
+    char* ws = reinterpret_cast<char*>(a.ws);
+    float* k_pooled = reinterpret_cast<float*>(ws + w.k_pooled);
+    float* mass_pooled = reinterpret_cast<float*>(ws + w.mass_pooled);
+    int32_t* kept_groups = reinterpret_cast<int32_t*>(ws + w.kept_groups);
+    uint32_t* sync = reinterpret_cast<uint32_t*>(ws + w.sync);
+    group_pool_kernel<T, D><<<dim3(w.G, a.H_k), kThreads, 0, s>>>(
+        (const T*)a.k_cache, a.head_stride, a.tok_stride, a.group, w.G, a.mass, a.L_k, k_pooled,
+        mass_pooled);
+    FC_LAUNCH_CHECK();
+    // the token-level scoring and selection, run on the groups
+    FcCompressArgs b = a;
+    b.k_cache = k_pooled; b.v_cache = k_pooled;
+    b.head_stride = (int64_t)w.G * D; b.tok_stride = D; b.dtype = FC_F32;
+    b.L_k = w.G; b.budget = w.Bg; b.mass = mass_pooled; b.kept = kept_groups; b.ws = ws + w.inner;
+    b.group = 1;
+    const int st = launch_typed<float, D>(b, s, false);
+    if (st != FC_OK) return st;
+    int gx = (int)(((int64_t)w.Bg * a.group + kThreads * 4 - 1) / (kThreads * 4));
+    gx = gx < 1 ? 1 : (gx > 256 ? 256 : gx);
+    expand_groups_kernel<<<dim3(gx, a.H_k), kThreads, 0, s>>>(kept_groups, w.Bg, a.group, a.kept, sync,
+                                                              a.H_k, w.ntile);
+    FC_LAUNCH_CHECK();
     constexpr int VPR = D * (int)sizeof(T) / 16;
     const int64_t hs = a.head_stride * (int64_t)sizeof(T) / 16, ts = a.tok_stride * (int64_t)sizeof(T) / 16;
     compact_rows_kernel<VPR><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
@@ -733,6 +841,10 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s) {
 }
 
 }  // namespace
+
+size_t fc_compress_grouped_workspace(int H_k, int L_k, int d, int budget, int group) {
+    return grouped_layout(H_k, L_k, d, budget, group).total;
+}
 
 size_t fc_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype) {
     return layout(H_k, L_k, d, budget, dtype).total;
@@ -744,6 +856,16 @@ int fc_launch_compress(const FcCompressArgs& a, hipStream_t s) {
         iota_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(a.kept, a.H_k, a.L_k);
         FC_LAUNCH_CHECK();
         return FC_OK;
+    }
+    if (a.group > 1) {
+        if (a.dtype == FC_BF16) {
+            if (a.d == 128) return launch_grouped<bf16_t, 128>(a, s);
+            if (a.d == 64) return launch_grouped<bf16_t, 64>(a, s);
+        } else {
+            if (a.d == 128) return launch_grouped<float, 128>(a, s);
+            if (a.d == 64) return launch_grouped<float, 64>(a, s);
+        }
+        return FC_UNSUPPORTED;
     }
     if (a.dtype == FC_BF16) {
         if (a.d == 128) return launch_typed<bf16_t, 128>(a, s);

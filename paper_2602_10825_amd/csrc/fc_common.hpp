@@ -136,6 +136,8 @@ struct FcCompressArgs {
     void* k_cache; void* v_cache; int64_t head_stride; int64_t tok_stride; fc_dtype dtype;
     int H_k; int d; int L_k; int budget; const float* mass; int pool_k; double lambda;
     int32_t* kept; void* ws;
+    int group;   // > 1: keys scored and kept in groups of this many consecutive tokens
 };
+size_t fc_compress_grouped_workspace(int H_k, int L_k, int d, int budget, int group);
 size_t fc_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype);
 int fc_launch_compress(const FcCompressArgs& a, hipStream_t s);

@@ -174,3 +174,20 @@ def test_uniform_decide_and_residual_apply_reject_bad_arguments(L):
     assert res(x=NULL) == INVALID and res(r=NULL) == INVALID and res(o=NULL) == INVALID
     assert res(idx=NULL) == INVALID and res(n=NULL) == INVALID
     assert res(A=0) == INVALID and res(A=17) == INVALID and res(ce=0) == INVALID and res(dtype=2) == INVALID
+
+
+def test_grouped_compress_rejects_bad_arguments(L):
+    def grp(**kw):
+        a = dict(kc=P, vc=P, hs=1024 * 128, ts=128, dtype=1, H=2, d=128, L_k=1000, budget=500, group=50,
+                 mass=P, pool=7, lam=0.07, kept=P, ws=P, wsb=1 << 26, stream=NULL)
+        a.update(kw)
+        return L.flowcache_kv_compress_grouped(a["kc"], a["vc"], a["hs"], a["ts"], a["dtype"], a["H"], a["d"],
+                                               a["L_k"], a["budget"], a["group"], a["mass"], a["pool"],
+                                               a["lam"], a["kept"], a["ws"], a["wsb"], a["stream"])
+
+    assert grp(group=0) == INVALID and grp(group=30) == INVALID        # 1000 % 30 != 0
+    assert grp(budget=510) == INVALID and grp(pool=4) == INVALID and grp(lam=1.5) == INVALID
+    assert grp(mass=NULL) == INVALID and grp(d=96) == UNSUPPORTED and grp(wsb=64) == WS_SMALL
+    assert L.flowcache_kv_compress_grouped_workspace(2, 1000, 128, 500, 30, 1) == 0
+    assert L.flowcache_kv_compress_grouped_workspace(2, 1000, 128, 500, 1, 1) == \
+        L.flowcache_kv_compress_workspace(2, 1000, 128, 500, 1)

@@ -302,6 +302,29 @@ def test_compress_on_strided_cache_prefix_leaves_the_rest_untouched():
     run_compress(wl, {"k": kfull, "v": vfull, "mass": c["mass"]}, wl.L_k, wl.budget)
 
 
+@pytest.mark.parametrize("wl,group,budget_groups,kind", [
+    (synth.MID_BF16, 50, 8, "normal"),            # 1000 tokens = 20 "frames" of 50
+    (synth.MID_BF16, 250, 2, "clustered"),        # 4 "chunks" of 250
+    (synth.MID_BF16, 8, 60, "heavy_dup"),
+    (synth.MID_F32, 70, 4, "normal"),             # 700 tokens, d = 64
+    (synth.MID_BF16, 1, 500, "normal"),           # group 1 = token granularity
+    (synth.MID_BF16, 50, 20, "normal"),           # budget covers everything: identity
+])
+def test_grouped_compress_matches_oracle(wl, group, budget_groups, kind):
+    c = synth.compress_inputs(wl, seed=7, kind=kind)
+    L_k, budget = wl.L_k, group * budget_groups
+    k, v = dev(c["k"], wl.dtype), dev(c["v"], wl.dtype)
+    mass = torch.from_numpy(c["mass"][:, :L_k].copy()).to(DEV)
+    kept = B.flowcache_kv_compress_grouped(k, v, L_k, budget, group, mass, 3, 0.3)
+    torch.cuda.synchronize()
+    rk, rk_k, rk_v, sc = O.kv_compress_grouped(c["k"], c["v"], L_k, budget, group, c["mass"][:, :L_k], 3, 0.3)
+    if sc is not None:
+        gaps = [O.boundary_gap(sc[h], budget_groups) for h in range(wl.H_k)]
+        assert all(g == 0.0 or g > 1e-12 for g in gaps), f"ambiguous boundary {gaps}"
+    assert np.array_equal(kept.cpu().numpy(), rk)
+    assert np.array_equal(B.to_host(k), rk_k) and np.array_equal(B.to_host(v), rk_v)
+
+
 # ------------------------------------------------------------------ the whole step, chained
 @pytest.mark.parametrize("wl,eps", [(synth.C1, None), (synth.C1, 0.0), (synth.MID_BF16, 0.0)])
 def test_full_step_chain(wl, eps):

@@ -189,3 +189,43 @@ def test_oracle_regression_fixture():
     assert now["mask"] == g["mask"]
     for key in ("l1rel", "out_sample", "mass_sample", "score_sample"):
         assert np.allclose(now[key], g[key], rtol=1e-12, atol=0), key
+
+
+# ---------------------------------------------------------------- grouped (frame / chunk) keys
+def test_grouped_compress_with_group_one_is_the_token_level_compress():
+    wl = synth.Workload("t", "bf16", 2, 2, 64, 1, 8, 96, 40)
+    c = synth.compress_inputs(wl, seed=5)
+    a = O.kv_compress(c["k"], c["v"], 96, 40, c["mass"], 5, 0.3)
+    b = O.kv_compress_grouped(c["k"], c["v"], 96, 40, 1, c["mass"], 5, 0.3)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+
+
+def test_grouped_compress_of_constant_groups_reduces_to_one_token_per_group():
+    # every group repeats one key and one mass value: its mean IS that key / value, so the
+    # kept groups are the tokens kv_compress keeps on the de-duplicated sequence
+    wl = synth.Workload("t", "f32", 2, 2, 64, 1, 8, 30, 12)
+    c = synth.compress_inputs(wl, seed=6)
+    g = 4
+    k = np.repeat(c["k"], g, axis=1)
+    v = np.repeat(c["v"], g, axis=1)
+    mass = np.repeat(c["mass"], g, axis=1)
+    kept_tok, _, _, _ = O.kv_compress(c["k"], c["v"], 30, 12, c["mass"], 3, 0.2)
+    kept, k_new, v_new, _ = O.kv_compress_grouped(k, v, 120, 48, g, mass, 3, 0.2)
+    want = (kept_tok[:, :, None] * g + np.arange(g)[None, None, :]).reshape(2, -1)
+    assert np.array_equal(kept, want)
+    for h in range(2):
+        assert np.array_equal(k_new[h, :48], k[h, kept[h]]) and np.array_equal(v_new[h, :48], v[h, kept[h]])
+
+
+def test_grouped_compress_hand_worked():
+    # 3 groups of 2 tokens in 2 dimensions; lambda = 1, pool 1: plain top-B of the group means
+    k = np.array([[[1, 0], [1, 0], [0, 1], [0, 3], [2, 2], [4, 4]]], np.float32)
+    v = np.arange(12, dtype=np.float32).reshape(1, 6, 2)
+    mass = np.array([[0.1, 0.3, 0.05, 0.05, 0.2, 0.3]], np.float32)      # group means .2, .05, .25
+    kept, k_new, v_new, sc = O.kv_compress_grouped(k, v, 6, 4, 2, mass, 1, 1.0)
+    assert kept.tolist() == [[0, 1, 4, 5]]
+    assert np.allclose(sc[0], [0.2, 0.05, 0.25])
+    assert v_new[0, :4].tolist() == [[0, 1], [2, 3], [8, 9], [10, 11]]
+    # identity when the budget covers everything
+    kept, k_new, _, _ = O.kv_compress_grouped(k, v, 6, 6, 2, mass, 1, 1.0)
+    assert kept.tolist() == [list(range(6))] and np.array_equal(k_new, k)
