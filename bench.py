@@ -34,7 +34,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak
 # HBM bytes per launch of the attention kernel on C2, from two rocprofv3 --pmc runs of this
 # script (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors calibrated on the 188 MB copy kernel
 # of the same runs; profiles/bench_C2_hbm_traffic.md)
-ATTEND_TRAFFIC_BYTES = {"C2-skyreels-v2-1.3B-like-bf16": int((913104.0 * 2.0 + 92596.9 * 1.0) * 1024)}
+ATTEND_TRAFFIC_BYTES = {"C2-skyreels-v2-1.3B-like-bf16": int((916401.8 * 2.0 + 88487.9 * 1.0) * 1024)}
 
 
 def parse():

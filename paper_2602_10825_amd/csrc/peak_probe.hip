@@ -2,6 +2,8 @@
 //   - bf16 matrix-core rate of a register-resident v_mfma_f32_32x32x16_bf16 loop, with
 //     constant and with random operands (clocks are power-limited, so the data matter),
 //   - HBM rate of a plain device copy and of a plain read.
+//   - matrix-core rate against wavefronts per SIMD and independent accumulator chains,
+//   - LDS read rate per compute unit for the attention kernel's two fragment patterns.
 // Stand-alone program (built next to the library); prints one line per measurement.
 #include <hip/hip_runtime.h>
 
@@ -46,6 +48,81 @@ __global__ __launch_bounds__(256) void mfma_loop(const bf16x8* in, float* out, l
         ticks[0] = clock64() - c0;
         ticks[1] = wall_clock64() - w0;
     }
+}
+
+// NCH independent accumulator chains per wavefront, constant operands
+template <int NCH>
+__global__ __launch_bounds__(256) void mfma_chains(float* out, int iters) {
+    bf16x8 a, b;
+    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)1.0f; b[i] = (__bf16)0.5f; }
+    f32x16 c[NCH];
+    for (int j = 0; j < NCH; ++j)
+        for (int i = 0; i < 16; ++i) c[j][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[j], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int j = 0; j < NCH; ++j) s += c[j][0];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+// 8 wavefronts per compute unit, 8 reads in flight each, the lane -> address patterns of the
+// attention kernel: MODE 0 ds_read_b128 of K fragments (272-byte rows), MODE 1
+// ds_read_b64_tr_b16 of V fragments (320-byte rows)
+template <int MODE>
+__global__ __launch_bounds__(512) void lds_reads(int* out, int iters, long long* ticks) {
+    __shared__ __attribute__((aligned(16))) short buf[64 * 160 + 64 * 136];
+    for (int i = threadIdx.x; i < 64 * 160 + 64 * 136; i += 512) buf[i] = (short)i;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31, hh = lane >> 5, l16 = lane & 15;
+    const unsigned kaddr = (unsigned)(size_t)(&buf[64 * 160]) + (l32 * 136 + 8 * hh) * 2;
+    const unsigned vaddr = (unsigned)(size_t)(&buf[0]) +
+                           ((hh * 4 + (l16 >> 2)) * 160 + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4) * 2;
+    int acc = 0;
+    const long long t0 = clock64();
+    for (int it = 0; it < iters; ++it) {
+        if (MODE == 0) {
+            i32x4 r[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r[j]) : "v"(kaddr), "n"(j * 32));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc ^= r[j].x;
+        } else {
+            i32x2 r[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r[j]) : "v"(vaddr), "n"(j * 64));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc ^= r[j].x;
+        }
+    }
+    const long long t1 = clock64();
+    out[blockIdx.x * 512 + threadIdx.x] = acc;
+    if (blockIdx.x == 0 && threadIdx.x == 0) ticks[0] = t1 - t0;
+}
+
+template <int NCH>
+static int run_chains(int blocks, float* dout, hipEvent_t e0, hipEvent_t e1) {
+    const int iters = 40000;
+    float ms = 0.f;
+    for (int rep = 0; rep < 3; ++rep) {
+        CK(hipEventRecord(e0));
+        mfma_chains<NCH><<<blocks, 256>>>(dout, iters);
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        CK(hipEventElapsedTime(&ms, e0, e1));
+    }
+    const double flops = (double)blocks * 4 * iters * NCH * 32768.0;
+    printf("mfma, constant operands, %d chain(s) per wavefront, %.0f wavefront(s) per SIMD: %.1f TFLOP/s\n", NCH,
+           blocks * 4 / 1024.0, flops / ms / 1e9);
+    return 0;
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ s, uint4* __restrict__ d, size_t n) {
@@ -107,8 +184,32 @@ int main() {
             }
             long long t[2];
             CK(hipMemcpy(t, dticks, 16, hipMemcpyDeviceToHost));
-            printf("mfma_f32_32x32x16_bf16, %s operands, %7.2f ms launch: %.1f TFLOP/s, shader clock %.0f MHz\n",
-                   mode ? "random" : "constant", ms, flops / ms / 1e9, (double)t[0] / (double)t[1] * wall_khz / 1e3);
+            (void)t;
+            (void)wall_khz;
+            printf("mfma_f32_32x32x16_bf16, %s operands, %7.2f ms launch: %.1f TFLOP/s\n",
+                   mode ? "random" : "constant", ms, flops / ms / 1e9);
+        }
+    }
+
+    if (run_chains<1>(256, dout, e0, e1) || run_chains<1>(512, dout, e0, e1) ||
+        run_chains<2>(256, dout, e0, e1) || run_chains<4>(256, dout, e0, e1) ||
+        run_chains<4>(512, dout, e0, e1))
+        return 1;
+    {
+        int* di;
+        CK(hipMalloc(&di, 256 * 512 * sizeof(int)));
+        const int iters = 20000;
+        for (int mode = 0; mode < 2; ++mode) {
+            for (int rep = 0; rep < 2; ++rep) {
+                if (mode == 0) lds_reads<0><<<256, 512>>>(di, iters, dticks);
+                else lds_reads<1><<<256, 512>>>(di, iters, dticks);
+                CK(hipDeviceSynchronize());
+            }
+            long long tk;
+            CK(hipMemcpy(&tk, dticks, 8, hipMemcpyDeviceToHost));
+            printf("LDS reads, %s: %.1f bytes/clk per compute unit\n",
+                   mode ? "ds_read_b64_tr_b16 (V fragment pattern)" : "ds_read_b128 (K fragment pattern)",
+                   (double)iters * 8 * 512 * (mode ? 8 : 16) / (double)tk);
         }
     }
 
