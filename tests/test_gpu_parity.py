@@ -235,6 +235,24 @@ def test_mass_matches_oracle(wl, W):
     assert torch.equal(m2, res["mass"])
 
 
+@pytest.mark.parametrize("dtype,d,H_q,H_k,W,mass_len", [
+    ("bf16", 128, 2, 2, 1, 1), ("bf16", 128, 2, 1, 3, 31), ("bf16", 64, 4, 2, 64, 129),
+    ("bf16", 128, 2, 2, 65, 1025), ("bf16", 128, 1, 1, 130, 2049), ("f32", 64, 2, 2, 5, 257),
+])
+def test_standalone_mass_edge_sizes(dtype, d, H_q, H_k, W, mass_len):
+    """One key, fewer keys than a tile, one key past a tile / a block span; one row, 65 and 130
+    rows (two and three row groups); grouped heads."""
+    rng = np.random.default_rng(mass_len)
+    q = synth.to_storage(rng.standard_normal((W, H_q, d)).astype(np.float32), dtype)
+    k = synth.to_storage(rng.standard_normal((H_k, mass_len + 7, d)).astype(np.float32), dtype)
+    got = B.flowcache_attention_mass(dev(q, dtype), dev(k, dtype), mass_len).cpu().numpy().astype(np.float64)
+    ref = O.attention_mass(q, k, mass_len)
+    assert got.shape == ref.shape and np.all(got >= 0)
+    assert np.allclose(got.sum(1), 1.0, atol=1e-4)
+    rel = np.abs(got - ref).sum(1) / ref.sum(1)
+    assert rel.max() <= (1e-5 if dtype == "f32" else 1e-2)
+
+
 def test_mass_is_nan_when_last_chunk_is_not_recomputed():
     wl = synth.C1
     a = synth.attend_inputs(wl, seed=0)
