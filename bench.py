@@ -151,7 +151,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (every box has one MI355X); "
-              "run it with --gpus 1.  Head-sharding across GPUs is described in DESIGN.md.",
+              "run it with --gpus 1.  The path would shard by attention heads across GPUs.",
               file=sys.stderr)
         sys.exit(2)
     import torch
