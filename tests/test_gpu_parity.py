@@ -194,6 +194,20 @@ def test_attend_no_clean_context_and_nothing_to_recompute():
     assert got.shape[0] == 0
 
 
+@pytest.mark.parametrize("dtype,d,A,L_c,L_clean", [
+    ("bf16", 128, 1, 1, 0), ("bf16", 128, 2, 1, 1), ("bf16", 64, 3, 33, 63), ("bf16", 128, 2, 257, 64),
+    ("bf16", 128, 1, 64, 65), ("bf16", 128, 4, 31, 0), ("f32", 64, 2, 1, 1), ("f32", 128, 1, 65, 0),
+])
+def test_attend_edge_sizes(dtype, d, A, L_c, L_clean):
+    """One-row chunks, chunks and clean regions one short of / equal to / one past a 64-key tile
+    and a 256-row block, no clean context."""
+    wl = synth.Workload("edge", dtype, 2, 2, d, A, L_c, L_clean, max(1, L_clean // 2))
+    a = synth.attend_inputs(wl, seed=8)
+    rec = list(range(A))
+    got, ref, res, ref_lse, _, _ = run_attend(wl, a, rec)
+    check_attend(wl, got, ref, res, ref_lse, A)
+
+
 def test_attend_bf16_when_later_keys_dwarf_earlier_ones():
     """Key magnitudes grow along the cache, so the scores of later tiles exceed the exponent
     reference of the earlier ones by far more than 2^40: the kernel has to raise its reference
