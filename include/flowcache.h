@@ -276,6 +276,18 @@ int flowcache_kv_compress_grouped(void* k_cache, void* v_cache, int64_t kv_head_
 size_t flowcache_kv_compress_grouped_workspace(int H_k, int L_k, int d, int budget, int group,
                                                fc_dtype dtype);
 
+/*
+ * The in-place compaction orders its row tiles with bounded waits (a tile stores only after
+ * the lower tiles that still read its rows have loaded them).  Should such a wait ever run
+ * into its spin limit the kernel does not hang: it sets a status word in the workspace.  This
+ * returns the BYTE OFFSET of that uint32 inside the workspace of a compress call with the same
+ * arguments (group = 1 for flowcache_kv_compress): 0 after the call = all waits were served,
+ * non-zero = the contents of the caches are unspecified.  Only meaningful when budget < L_k
+ * (the identity case does not touch the workspace).  (size_t)-1 for invalid arguments.
+ */
+size_t flowcache_kv_compress_status_offset(int H_k, int L_k, int d, int budget, int group,
+                                           fc_dtype dtype);
+
 #ifdef __cplusplus
 }
 #endif

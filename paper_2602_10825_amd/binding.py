@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libflowcache.so")
 
 FC_F32, FC_BF16 = 0, 1
 FC_OK = 0
+FC_INVALID_ARGUMENT = 1
 FC_MAX_ACTIVE = 16
 
 EXPORTS = (
@@ -29,6 +30,7 @@ EXPORTS = (
     "flowcache_attention_mass", "flowcache_attention_mass_workspace",
     "flowcache_kv_compress", "flowcache_kv_compress_workspace",
     "flowcache_kv_compress_grouped", "flowcache_kv_compress_grouped_workspace",
+    "flowcache_kv_compress_status_offset",
     "flowcache_sched_state_bytes", "flowcache_sched_init", "flowcache_sched_capacity",
     "flowcache_sched_total_ticks", "flowcache_sched_next",
 )
@@ -91,6 +93,8 @@ def lib() -> ctypes.CDLL:
     L.flowcache_kv_compress_grouped.restype = c_int
     L.flowcache_kv_compress_grouped.argtypes = [c_vp, c_vp, c_i64, c_i64, c_int, c_int, c_int, c_int, c_int,
                                                 c_int, c_vp, c_int, c_d, c_vp, c_vp, c_sz, c_vp]
+    L.flowcache_kv_compress_status_offset.restype = c_sz
+    L.flowcache_kv_compress_status_offset.argtypes = [c_int] * 6
     L.flowcache_sched_state_bytes.restype = c_sz
     L.flowcache_sched_state_bytes.argtypes = []
     L.flowcache_sched_init.restype = c_int
@@ -334,8 +338,16 @@ def flowcache_kv_compress_grouped(k_cache: torch.Tensor, v_cache: torch.Tensor, 
 
 
 # --------------------------------------------------------------------------------------
+def kv_compress_status(workspace: torch.Tensor, H_k: int, L_k: int, d: int, budget: int,
+                       dtype_code: int, group: int = 1) -> int:
+    """Status word of the last compress call that used ``workspace`` (synchronises): 0 = ok."""
+    off = lib().flowcache_kv_compress_status_offset(H_k, L_k, d, budget, group, dtype_code)
+    if off == ctypes.c_size_t(-1).value:
+        raise FlowCacheError("flowcache_kv_compress_status_offset", FC_INVALID_ARGUMENT)
+    return int(workspace[off:off + 4].view(torch.int32).item())
+
+
 # ---- host-side tick scheduler (flowcache_sched.h) ------------------------------------------
-FC_MAX_ACTIVE = 16
 FC_SCHED_DONE = 5
 
 

@@ -267,6 +267,14 @@ int flowcache_kv_compress_grouped(void* k_cache, void* v_cache, int64_t kv_head_
     return fc_launch_compress(c, (hipStream_t)stream);
 }
 
+size_t flowcache_kv_compress_status_offset(int H_k, int L_k, int d, int budget, int group,
+                                           fc_dtype dtype) {
+    if (H_k < 1 || L_k < 1 || budget < 1 || group < 1 || (d != 64 && d != 128) || bad_dtype(dtype))
+        return (size_t)-1;
+    if (L_k % group != 0 || budget % group != 0) return (size_t)-1;
+    return fc_compress_status_offset(H_k, L_k, d, budget, group, dtype);
+}
+
 size_t flowcache_kv_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype) {
     if (H_k < 1 || L_k < 1 || budget < 1 || (d != 64 && d != 128) || bad_dtype(dtype)) return 0;
     return fc_compress_workspace(H_k, L_k, d, budget, dtype);

@@ -846,6 +846,11 @@ size_t fc_compress_grouped_workspace(int H_k, int L_k, int d, int budget, int gr
     return grouped_layout(H_k, L_k, d, budget, group).total;
 }
 
+size_t fc_compress_status_offset(int H_k, int L_k, int d, int budget, int group, fc_dtype dtype) {
+    if (group > 1) return grouped_layout(H_k, L_k, d, budget, group).sync;
+    return layout(H_k, L_k, d, budget, dtype).sync;
+}
+
 size_t fc_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype) {
     return layout(H_k, L_k, d, budget, dtype).total;
 }

@@ -139,5 +139,6 @@ struct FcCompressArgs {
     int group;   // > 1: keys scored and kept in groups of this many consecutive tokens
 };
 size_t fc_compress_grouped_workspace(int H_k, int L_k, int d, int budget, int group);
+size_t fc_compress_status_offset(int H_k, int L_k, int d, int budget, int group, fc_dtype dtype);
 size_t fc_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype);
 int fc_launch_compress(const FcCompressArgs& a, hipStream_t s);

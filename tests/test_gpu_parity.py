@@ -324,6 +324,25 @@ def test_compress_exact_ties_and_bf16_d64():
     assert kept.cpu().numpy()[0].tolist() == list(range(32))
 
 
+def test_compress_status_word_is_clear_after_normal_calls():
+    wl = synth.MID_BF16
+    c = synth.compress_inputs(wl, seed=9)
+    k, v = dev(c["k"], wl.dtype), dev(c["v"], wl.dtype)
+    mass = torch.from_numpy(c["mass"][:, :wl.L_k].copy()).to(DEV)
+    L = B.lib()
+    ws = torch.full((L.flowcache_kv_compress_workspace(wl.H_k, wl.L_k, wl.d, wl.budget, B.FC_BF16),), 0xFF,
+                    dtype=torch.uint8, device=DEV)           # the call must reset the word itself
+    B.flowcache_kv_compress(k, v, wl.L_k, wl.budget, mass, workspace=ws)
+    assert B.kv_compress_status(ws, wl.H_k, wl.L_k, wl.d, wl.budget, B.FC_BF16) == 0
+    k, v = dev(c["k"], wl.dtype), dev(c["v"], wl.dtype)
+    ws = torch.full((L.flowcache_kv_compress_grouped_workspace(wl.H_k, wl.L_k, wl.d, 500, 50, B.FC_BF16),),
+                    0xFF, dtype=torch.uint8, device=DEV)
+    B.flowcache_kv_compress_grouped(k, v, wl.L_k, 500, 50, mass, workspace=ws)
+    assert B.kv_compress_status(ws, wl.H_k, wl.L_k, wl.d, 500, B.FC_BF16, group=50) == 0
+    with pytest.raises(B.FlowCacheError):
+        B.kv_compress_status(ws, wl.H_k, wl.L_k, wl.d, 510, B.FC_BF16, group=50)
+
+
 def test_compress_on_strided_cache_prefix_leaves_the_rest_untouched():
     wl = synth.MID_BF16
     c = synth.compress_inputs(wl, seed=4)
