@@ -168,12 +168,12 @@ constexpr int kNT = 256;
 constexpr float kPosBig = 1.0e30f;
 
 template <int D>
-struct MassSmem {
+struct __attribute__((aligned(16))) MassSmem {
     // rows padded by 16 bytes: the 16-byte fragment reads of 32 consecutive rows then fall
-    // on distinct LDS banks
-    bf16_t q[kRowGroup][D + 8];
-    union {
-        bf16_t k[kTile][D + 8];
+    // on distinct LDS banks.  The 16-byte alignment is what lets them be single ds_read_b128.
+    __attribute__((aligned(16))) bf16_t q[kRowGroup][D + 8];
+    union __attribute__((aligned(16))) {
+        __attribute__((aligned(16))) bf16_t k[kTile][D + 8];
         float merge[2][32][kTile + 1];   // per-lane (max, sum) of 32 rows, after the tile loop
     };
     float lse[kRowGroup];
@@ -242,12 +242,12 @@ __device__ __forceinline__ void tile_scores(const MassSmem<D>& sm, int wave, int
 }
 
 template <int D>
-__global__ __launch_bounds__(kNT) void mass_stats_bf16_kernel(FcMassArgs a, int w0, int nw, int np,
+__global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, int nrg, int np,
                                                               float* __restrict__ pm,
                                                               float* __restrict__ pl) {
     int64_t row0;
     if (!resolve_rows(a, row0)) return;
-    __shared__ MassSmem<D> sm;
+    __shared__ __attribute__((aligned(16))) MassSmem<D> sm;
     const int h = blockIdx.y;
     const int hk = h / (a.H_q / a.H_k);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -256,6 +256,12 @@ __global__ __launch_bounds__(kNT) void mass_stats_bf16_kernel(FcMassArgs a, int 
     const int left = a.mass_len - jb;
     const int nt = left >= kSpan ? kTilesPerBlock : (left + kTile - 1) / kTile;
     const float c2 = a.scale * kLog2e;
+    // row groups of 64 observation rows, one after the other: the block re-reads its own key
+    // span (resident in L2 / Infinity Cache after the first group) instead of the whole K
+    for (int rg = 0; rg < nrg; ++rg) {
+    const int w0 = rg * kRowGroup;
+    const int nw = (a.W - w0 < kRowGroup) ? a.W - w0 : kRowGroup;
+    __syncthreads();
     stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
     u32x4_native kr[D / 16];
     fetch_ktile<D>(a, kh, jb, kr);
@@ -315,17 +321,17 @@ __global__ __launch_bounds__(kNT) void mass_stats_bf16_kernel(FcMassArgs a, int 
             mx = mn;
         }
         if (part == 0) {
-            pm[((int64_t)h * kRowGroup + rb * 32 + row) * np + blockIdx.x] = mx;
-            pl[((int64_t)h * kRowGroup + rb * 32 + row) * np + blockIdx.x] = sum;
+            pm[(((int64_t)h * nrg + rg) * kRowGroup + rb * 32 + row) * np + blockIdx.x] = mx;
+            pl[(((int64_t)h * nrg + rg) * kRowGroup + rb * 32 + row) * np + blockIdx.x] = sum;
         }
     }
+    }   // row groups
 }
 
 template <int D>
-__global__ __launch_bounds__(kNT) void mass_cols_bf16_kernel(FcMassArgs a, int w0, int nw, int np,
+__global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, int nrg, int np,
                                                              const float* __restrict__ pm,
-                                                             const float* __restrict__ pl,
-                                                             int first) {
+                                                             const float* __restrict__ pl) {
     const int hk = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int jb = blockIdx.x * kSpan;
@@ -337,20 +343,23 @@ __global__ __launch_bounds__(kNT) void mass_cols_bf16_kernel(FcMassArgs a, int w
             a.mass[(int64_t)hk * a.mass_len + jb + i] = __uint_as_float(0x7fc00000u);
         return;
     }
-    __shared__ MassSmem<D> sm;
+    __shared__ __attribute__((aligned(16))) MassSmem<D> sm;
     const int G = a.H_q / a.H_k;
     const bf16_t* kh = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
     const int nt = (nkeys + kTile - 1) / kTile;
     const float c2 = a.scale * kLog2e;
     for (int i = tid; i < kSpan; i += kNT) sm.acc[i] = 0.f;
+    for (int rg = 0; rg < nrg; ++rg)
     for (int g = 0; g < G; ++g) {
         const int h = hk * G + g;
+        const int w0 = rg * kRowGroup;
+        const int nw = (a.W - w0 < kRowGroup) ? a.W - w0 : kRowGroup;
         __syncthreads();
         stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
         if (tid < kRowGroup) {
             // log2-sum-exp of row tid over all keys: the blocks' partials in index order
-            const float* m = pm + ((int64_t)h * kRowGroup + tid) * np;
-            const float* l = pl + ((int64_t)h * kRowGroup + tid) * np;
+            const float* m = pm + (((int64_t)h * nrg + rg) * kRowGroup + tid) * np;
+            const float* l = pl + (((int64_t)h * nrg + rg) * kRowGroup + tid) * np;
             float mx = kNegBig;
             for (int i = 0; i < np; ++i) mx = fmaxf(mx, m[i]);
             float sum = 0.f;
@@ -386,24 +395,20 @@ __global__ __launch_bounds__(kNT) void mass_cols_bf16_kernel(FcMassArgs a, int w
     __syncthreads();
     const float inv = 1.0f / (float)(a.W * G);
     for (int i = tid; i < nkeys; i += kNT) {
-        float* dst = a.mass + (int64_t)hk * a.mass_len + jb + i;
-        const float c = sm.acc[i] * inv;
-        *dst = first ? c : *dst + c;
+        a.mass[(int64_t)hk * a.mass_len + jb + i] = sm.acc[i] * inv;
     }
 }
 
 template <int D>
 int launch_bf16(const FcMassArgs& a, hipStream_t s) {
     const int np = (a.mass_len + kSpan - 1) / kSpan;
+    const int nrg = (a.W + kRowGroup - 1) / kRowGroup;
     float* pm = reinterpret_cast<float*>(a.ws);
-    float* pl = pm + (size_t)a.H_q * kRowGroup * np;
-    for (int w0 = 0; w0 < a.W; w0 += kRowGroup) {
-        const int nw = (a.W - w0 < kRowGroup) ? a.W - w0 : kRowGroup;
-        mass_stats_bf16_kernel<D><<<dim3(np, a.H_q), kNT, 0, s>>>(a, w0, nw, np, pm, pl);
-        FC_LAUNCH_CHECK();
-        mass_cols_bf16_kernel<D><<<dim3(np, a.H_k), kNT, 0, s>>>(a, w0, nw, np, pm, pl, w0 == 0 ? 1 : 0);
-        FC_LAUNCH_CHECK();
-    }
+    float* pl = pm + (size_t)a.H_q * nrg * kRowGroup * np;
+    mass_stats_bf16_kernel<D><<<dim3(np, a.H_q), kNT, 0, s>>>(a, nrg, np, pm, pl);
+    FC_LAUNCH_CHECK();
+    mass_cols_bf16_kernel<D><<<dim3(np, a.H_k), kNT, 0, s>>>(a, nrg, np, pm, pl);
+    FC_LAUNCH_CHECK();
     return FC_OK;
 }
 
@@ -429,10 +434,15 @@ int launch_typed(const FcMassArgs& a, hipStream_t s) {
 }  // namespace
 
 size_t fc_mass_workspace(int W, int H_q, int mass_len) {
-    (void)W;
+    // fp32 path: one row group at a time, a partial per wavefront of 64 keys
     const size_t nkb = ((size_t)mass_len + kKeys - 1) / kKeys;
     const size_t np = nkb * (kKeys / FC_WAVE);
-    return fc_align_up(((size_t)2 * H_q * kRowGroup * np + (size_t)H_q * kRowGroup) * sizeof(float));
+    const size_t f32 = ((size_t)2 * H_q * kRowGroup * np + (size_t)H_q * kRowGroup) * sizeof(float);
+    // bf16 path: all row groups in one launch, a partial per block span of keys
+    const size_t nrg = ((size_t)(W > 0 ? W : 1) + kRowGroup - 1) / kRowGroup;
+    const size_t nps = ((size_t)mass_len + kSpan - 1) / kSpan;
+    const size_t bf16 = (size_t)2 * H_q * nrg * kRowGroup * nps * sizeof(float);
+    return fc_align_up(f32 > bf16 ? f32 : bf16);
 }
 
 int fc_launch_mass(const FcMassArgs& a, hipStream_t s) {
