@@ -107,43 +107,48 @@ __global__ __launch_bounds__(kThreads) void decide_finalize_kernel(
     int warmup_m, double eps, double* __restrict__ acc, double* __restrict__ l1rel,
     uint8_t* __restrict__ mask, int32_t* __restrict__ idx, int32_t* __restrict__ n_rec,
     int uniform) {
-    __shared__ double sh[2][kThreads];
     __shared__ double tot[2][FC_MAX_ACTIVE];
+    __shared__ double acc_in[FC_MAX_ACTIVE];
+    __shared__ int32_t step_in[FC_MAX_ACTIVE];
     const int tid = threadIdx.x;
-    for (int i = 0; i < A; ++i) {
+    // the policy's own inputs are requested first, so that their latency overlaps the sums
+    if (tid >= kThreads - FC_MAX_ACTIVE) {
+        const int i = tid - (kThreads - FC_MAX_ACTIVE);
+        if (i < A) step_in[i] = step_idx[i];
+        if (i < (uniform ? 1 : A)) acc_in[i] = acc[i];
+    }
+    // one wavefront per chunk (chunks i, i + 4, ...): lane-strided sums of the block partials,
+    // then a fixed shuffle tree -- no block-wide barriers inside the loop
+    const int wave = tid / FC_WAVE, lane = tid % FC_WAVE;
+    for (int i = wave; i < A; i += kThreads / FC_WAVE) {
         double a = 0.0, b = 0.0;
-        for (int k = tid; k < bpc; k += kThreads) {
+        for (int k = lane; k < bpc; k += FC_WAVE) {
             a += partial[2 * ((int64_t)i * bpc + k)];
             b += partial[2 * ((int64_t)i * bpc + k) + 1];
         }
-        sh[0][tid] = a;
-        sh[1][tid] = b;
-        __syncthreads();
-        for (int s = kThreads / 2; s > 0; s >>= 1) {
-            if (tid < s) { sh[0][tid] += sh[0][tid + s]; sh[1][tid] += sh[1][tid + s]; }
-            __syncthreads();
-        }
-        if (tid == 0) { tot[0][i] = sh[0][0]; tot[1][i] = sh[1][0]; }
-        __syncthreads();
+        a = wave_sum(a);
+        b = wave_sum(b);
+        if (lane == 0) { tot[0][i] = a; tot[1][i] = b; }
     }
+    __syncthreads();
     if (tid == 0 && uniform) {
         // Fig. 2, top: the chunks past warm-up share one metric, accumulator and decision
         double num = 0.0, den = 0.0;
         int old = 0;
         for (int i = 0; i < A; ++i)
-            if (step_idx[i] >= warmup_m) { num += tot[0][i]; den += tot[1][i]; ++old; }
+            if (step_in[i] >= warmup_m) { num += tot[0][i]; den += tot[1][i]; ++old; }
         double f = 0.0;
         double rel = __longlong_as_double(0x7ff8000000000000LL);   // NaN: no chunk to measure
         if (old) {
             rel = (den == 0.0) ? __longlong_as_double(0x7ff0000000000000LL) : num / den;
-            const double a = acc[0] + rel;
+            const double a = acc_in[0] + rel;
             f = (a > eps) ? 0.0 : a;
         }
         acc[0] = f;
         if (l1rel) l1rel[0] = rel;
         int cnt = 0;
         for (int i = 0; i < A; ++i) {
-            const bool rec = (step_idx[i] < warmup_m) || (f == 0.0);
+            const bool rec = (step_in[i] < warmup_m) || (f == 0.0);
             mask[i] = rec ? 1 : 0;
             if (rec) idx[cnt++] = i;
         }
@@ -155,10 +160,10 @@ __global__ __launch_bounds__(kThreads) void decide_finalize_kernel(
             const double num = tot[0][i], den = tot[1][i];
             const double rel = (den == 0.0) ? __longlong_as_double(0x7ff0000000000000LL) : num / den;
             double f;
-            if (step_idx[i] < warmup_m) {
+            if (step_in[i] < warmup_m) {
                 f = 0.0;                       // case 1: warm-up steps never reuse
             } else {
-                const double a = acc[i] + rel;
+                const double a = acc_in[i] + rel;
                 f = (a > eps) ? 0.0 : a;       // case 2 / case 3
             }
             const bool rec = (f == 0.0);
