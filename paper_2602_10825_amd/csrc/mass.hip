@@ -356,16 +356,42 @@ __global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, in
         const int nw = (a.W - w0 < kRowGroup) ? a.W - w0 : kRowGroup;
         __syncthreads();
         stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
-        if (tid < kRowGroup) {
-            // log2-sum-exp of row tid over all keys: the blocks' partials in index order
-            const float* m = pm + (((int64_t)h * nrg + rg) * kRowGroup + tid) * np;
-            const float* l = pl + (((int64_t)h * nrg + rg) * kRowGroup + tid) * np;
-            float mx = kNegBig;
-            for (int i = 0; i < np; ++i) mx = fmaxf(mx, m[i]);
-            float sum = 0.f;
-            for (int i = 0; i < np; ++i) sum += l[i] * __builtin_amdgcn_exp2f(m[i] - mx);
+        {
+            // log2-sum-exp of every row over all keys from the blocks' partials: four lanes per
+            // row take every fourth partial (loads batched four deep), then merge in a fixed order
+            const int row = tid >> 2, part = tid & 3;
+            const float* m = pm + (((int64_t)h * nrg + rg) * kRowGroup + row) * np;
+            const float* l = pl + (((int64_t)h * nrg + rg) * kRowGroup + row) * np;
+            float mx = kNegBig, sum = 0.f;
+            for (int i0 = part; i0 < np; i0 += 16) {
+                float mi[4], li[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + 4 * u;
+                    mi[u] = i < np ? m[i] : kNegBig;
+                    li[u] = i < np ? l[i] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float mn = fmaxf(mx, mi[u]);
+                    sum = sum * __builtin_amdgcn_exp2f(mx - mn) + li[u] * __builtin_amdgcn_exp2f(mi[u] - mn);
+                    mx = mn;
+                }
+            }
+#pragma unroll
+            for (int o = 1; o < 4; o <<= 1) {
+                const float mo = __shfl_xor(mx, o, FC_WAVE), so = __shfl_xor(sum, o, FC_WAVE);
+                const float mn = fmaxf(mx, mo);
+                // the lower lane's term first on both sides, so partners agree bit for bit
+                const float lo = (part & o) ? so * __builtin_amdgcn_exp2f(mo - mn)
+                                            : sum * __builtin_amdgcn_exp2f(mx - mn);
+                const float hi = (part & o) ? sum * __builtin_amdgcn_exp2f(mx - mn)
+                                            : so * __builtin_amdgcn_exp2f(mo - mn);
+                sum = lo + hi;
+                mx = mn;
+            }
             // padding rows get a huge normaliser: their terms vanish
-            sm.lse[tid] = tid < nw ? mx + __builtin_amdgcn_logf(sum) : kPosBig;
+            if (part == 0) sm.lse[row] = row < nw ? mx + __builtin_amdgcn_logf(sum) : kPosBig;
         }
         u32x4_native kr[D / 16];
         fetch_ktile<D>(a, kh, jb, kr);
