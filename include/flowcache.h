@@ -41,6 +41,10 @@
  *    No exception crosses the boundary; the library keeps no global state.
  *  - dtype FC_F32: float tensors, fp32 arithmetic.  FC_BF16: bfloat16 tensors, bf16 x bf16
  *    -> fp32 matrix-core products, fp32 softmax state, bf16 output.
+ *  - The recompute list (recompute_idx, n_recompute) lives on the device, so the host
+ *    cannot check it: the kernels do.  A count above A is cut to A and an entry outside
+ *    [0, A) is skipped (nothing is read or written for it); no out-of-range access follows
+ *    from a bad list.
  *  - Decisions (reuse masks) and kept-token indices are taken in float64 and are meant to
  *    be bit-reproducible run to run: no floating-point atomics are used anywhere.
  */
@@ -140,8 +144,9 @@ int flowcache_uniform_decide(const void* x_cur, const void* x_prev, fc_dtype dty
  *
  *   x_cur      [dev] [A, chunk_elems] input of the stack this tick
  *   y_compact  [dev] [A, chunk_elems] compact: block r = output for chunk recompute_idx[r]
- *                    (blocks r >= *n_recompute are not read); may be NULL only if the
- *                    caller guarantees *n_recompute == 0
+ *                    (blocks r >= *n_recompute are not read); may be NULL when nothing is
+ *                    recomputed this tick: then the list is not consulted and every chunk
+ *                    is treated as reused
  *   residual   [dev] [A, chunk_elems] in/out cache
  *   out        [dev] [A, chunk_elems] full-layout output of the stack; may alias x_cur
  *   recompute_idx, n_recompute [dev] as written by the decide calls

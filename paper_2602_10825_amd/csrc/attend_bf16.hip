@@ -123,10 +123,11 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
     const int rank = slot / per;
     const int item = xcd * per + slot % per;
     if (item >= a.H_q * tiles) return;
-    const int R = *a.n_rec;
-    if (rank >= R) return;
+    const int R = min(*a.n_rec, a.A);         // a count or an entry outside the valid range
+    if (rank >= R) return;                    // (a caller's mistake) is skipped, never followed
     const int r = R - 1 - rank;               // heaviest (latest) chunk first
     const int c = a.rec_idx[r];
+    if ((unsigned)c >= (unsigned)a.A) return;
     const int h = item / tiles, tile = item % tiles;
     const int hk = h / (a.H_q / a.H_k);
 

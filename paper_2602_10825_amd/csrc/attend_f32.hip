@@ -17,6 +17,7 @@ __global__ __launch_bounds__(256) void scatter_kv_kernel(
     const int r = blockIdx.y;
     if (r >= *args.n_rec) return;
     const int c = args.rec_idx[r];
+    if ((unsigned)c >= (unsigned)args.A) return;   // not a chunk: skipped, never followed
     const int64_t slot = args.active_off[c];
     const int64_t per_chunk = (int64_t)L_c * H_k * vpr;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -40,6 +41,7 @@ __global__ __launch_bounds__(kRows) void attend_f32_kernel(FcAttendArgs a) {
     const int r = blockIdx.z;
     if (r >= *a.n_rec) return;
     const int c = a.rec_idx[r];
+    if ((unsigned)c >= (unsigned)a.A) return;
     const int h = blockIdx.y;
     const int hk = h / (a.H_q / a.H_k);
     const int tid = threadIdx.x;

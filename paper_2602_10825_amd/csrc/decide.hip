@@ -183,6 +183,7 @@ __global__ __launch_bounds__(kThreads) void gather_chunks_kernel(
     const int r = blockIdx.y;
     if (r >= *n_rec) return;
     const int c = idx[r];
+    if ((unsigned)c >= gridDim.y) return;
     const uint4* s = src + (int64_t)c * chunk_vecs;
     uint4* d = dst + (int64_t)r * chunk_vecs;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
@@ -197,6 +198,7 @@ __global__ __launch_bounds__(kThreads) void gather_chunks_bytes_kernel(
     const int r = blockIdx.y;
     if (r >= *n_rec) return;
     const int c = idx[r];
+    if ((unsigned)c >= gridDim.y) return;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < chunk_bytes; i += stride)
         dst[(int64_t)r * chunk_bytes + i] = src[(int64_t)c * chunk_bytes + i];

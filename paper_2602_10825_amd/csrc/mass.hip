@@ -45,7 +45,7 @@ struct RowSrc {
 __device__ __forceinline__ bool resolve_rows(const FcMassArgs& a, int64_t& row0) {
     if (a.n_rec) {
         const int R = *a.n_rec;
-        if (R <= 0 || a.rec_idx[R - 1] != a.A - 1) return false;
+        if (R <= 0 || R > a.A || a.rec_idx[R - 1] != a.A - 1) return false;
         row0 = (int64_t)R * a.L_c - a.W;
     } else {
         row0 = 0;
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kRowGroup) void mass_lse_kernel(const float* __rest
                                                              const int32_t* rec_idx, int A) {
     if (n_rec) {
         const int R = *n_rec;
-        if (R <= 0 || rec_idx[R - 1] != A - 1) return;
+        if (R <= 0 || R > A || rec_idx[R - 1] != A - 1) return;
     }
     const int h = blockIdx.x, w = threadIdx.x;
     if (w >= nw) return;

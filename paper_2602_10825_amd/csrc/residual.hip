@@ -43,7 +43,7 @@ template <> __device__ __forceinline__ uint4 pack16<bf16_t>(const double (&v)[8]
 
 // compact row of chunk c in the recompute list, or -1
 __device__ __forceinline__ int compact_row(const int32_t* idx, const int32_t* n_rec, int c) {
-    const int R = *n_rec;
+    const int R = min(*n_rec, (int)gridDim.y);   // the list never has more entries than chunks
     for (int r = 0; r < R; ++r)
         if (idx[r] == c) return r;
     return -1;
@@ -56,7 +56,8 @@ __global__ __launch_bounds__(kThreads) void residual_apply_kernel(
     const int32_t* __restrict__ n_rec) {
     constexpr int V = Elem<T>::kVec;
     const int c = blockIdx.y;
-    const int r = compact_row(idx, n_rec, c);
+    // without y_compact there is nothing to store: every chunk is treated as reused
+    const int r = y_compact ? compact_row(idx, n_rec, c) : -1;
     const T* x = x_cur + (int64_t)c * chunk_elems;
     T* res = residual + (int64_t)c * chunk_elems;
     T* o = out + (int64_t)c * chunk_elems;

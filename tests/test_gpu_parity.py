@@ -194,6 +194,43 @@ def test_attend_no_clean_context_and_nothing_to_recompute():
     assert got.shape[0] == 0
 
 
+@pytest.mark.parametrize("wl", [synth.MID_BF16, synth.MID_F32])
+def test_malformed_recompute_list_is_skipped_not_followed(wl):
+    """A count above A is cut to A and entries outside [0, A) are skipped by the kernels' own
+    checks: the valid entry gives the bits of the well-formed call, nothing else is touched."""
+    a = synth.attend_inputs(wl, seed=11)
+    n_rows = wl.A * wl.L_c
+    rng = np.random.default_rng(0)
+    q = dev(rng.standard_normal((n_rows, wl.H_q, wl.d)), wl.dtype)
+    kn = dev(rng.standard_normal((n_rows, wl.H_k, wl.d)), wl.dtype)
+    vn = dev(rng.standard_normal((n_rows, wl.H_k, wl.d)), wl.dtype)
+    outs = []
+    for lst, cnt in (([1, -1, -1], 1), ([1, 99, -3], 9)):
+        kc, vc = dev(a["k_cache"], wl.dtype), dev(a["v_cache"], wl.dtype)
+        out0 = torch.full_like(q, 7.0)
+        idx = torch.tensor(lst, dtype=torch.int32, device=DEV)
+        n = torch.tensor([cnt], dtype=torch.int32, device=DEV)
+        B.flowcache_attend(q, kn, vn, kc, vc, wl.L_c, wl.L_clean, a["active_off"], idx, n, out=out0,
+                           want_lse=False)
+        x = dev(rng.standard_normal((wl.A, 1000)), wl.dtype) if not outs else outs[0][3]
+        y = dev(rng.standard_normal((wl.A, 1000)), wl.dtype) if not outs else outs[0][4]
+        res = torch.ones_like(x)
+        full = B.flowcache_residual_apply(x, y, res, idx, n)
+        torch.cuda.synchronize()
+        outs.append((B.to_host(out0), B.to_host(kc), B.to_host(vc), x, y, B.to_host(res), B.to_host(full)))
+    good, bad = outs
+    for i in (0, 1, 2, 5, 6):
+        assert np.array_equal(good[i], bad[i])
+    assert np.all(O.widen(bad[0])[wl.L_c:] == 7.0)
+    # no y_compact: the list is not consulted, every chunk is reused
+    x, res = good[3], torch.ones_like(good[3])
+    idx = torch.tensor([1, 0, 2], dtype=torch.int32, device=DEV)
+    n = torch.tensor([2], dtype=torch.int32, device=DEV)
+    full = B.flowcache_residual_apply(x, None, res, idx, n)
+    ref_res, ref_full = O.residual_apply(B.to_host(x), None, B.to_host(res), [])
+    assert np.array_equal(B.to_host(full), ref_full) and np.array_equal(B.to_host(res), ref_res)
+
+
 @pytest.mark.parametrize("dtype,d,A,L_c,L_clean", [
     ("bf16", 128, 1, 1, 0), ("bf16", 128, 2, 1, 1), ("bf16", 64, 3, 33, 63), ("bf16", 128, 2, 257, 64),
     ("bf16", 128, 1, 64, 65), ("bf16", 128, 4, 31, 0), ("f32", 64, 2, 1, 1), ("f32", 128, 1, 65, 0),
