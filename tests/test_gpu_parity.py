@@ -200,10 +200,14 @@ def test_malformed_recompute_list_is_skipped_not_followed(wl):
     checks: the valid entry gives the bits of the well-formed call, nothing else is touched."""
     a = synth.attend_inputs(wl, seed=11)
     n_rows = wl.A * wl.L_c
-    rng = np.random.default_rng(0)
-    q = dev(rng.standard_normal((n_rows, wl.H_q, wl.d)), wl.dtype)
-    kn = dev(rng.standard_normal((n_rows, wl.H_k, wl.d)), wl.dtype)
-    vn = dev(rng.standard_normal((n_rows, wl.H_k, wl.d)), wl.dtype)
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(0)
+
+    def randn(*shape):
+        return torch.randn(shape, device=DEV, generator=gen).to(tdt)
+
+    q, kn, vn = randn(n_rows, wl.H_q, wl.d), randn(n_rows, wl.H_k, wl.d), randn(n_rows, wl.H_k, wl.d)
     outs = []
     for lst, cnt in (([1, -1, -1], 1), ([1, 99, -3], 9)):
         kc, vc = dev(a["k_cache"], wl.dtype), dev(a["v_cache"], wl.dtype)
@@ -212,8 +216,8 @@ def test_malformed_recompute_list_is_skipped_not_followed(wl):
         n = torch.tensor([cnt], dtype=torch.int32, device=DEV)
         B.flowcache_attend(q, kn, vn, kc, vc, wl.L_c, wl.L_clean, a["active_off"], idx, n, out=out0,
                            want_lse=False)
-        x = dev(rng.standard_normal((wl.A, 1000)), wl.dtype) if not outs else outs[0][3]
-        y = dev(rng.standard_normal((wl.A, 1000)), wl.dtype) if not outs else outs[0][4]
+        x = randn(wl.A, 1000) if not outs else outs[0][3]
+        y = randn(wl.A, 1000) if not outs else outs[0][4]
         res = torch.ones_like(x)
         full = B.flowcache_residual_apply(x, y, res, idx, n)
         torch.cuda.synchronize()
