@@ -173,7 +173,7 @@ int flowcache_residual_apply(const void* x_cur, const void* y_compact, void* res
  *                  copied into slot active_off[recompute_idx[r]] of the caches.
  *   k_cache,
  *   v_cache  [dev] head-major: element (h, pos, e) at h*kv_head_stride + pos*kv_tok_stride + e
- *                  (strides in elements; kv_tok_stride >= d and a multiple of 8,
+ *                  (strides in elements; d <= kv_tok_stride <= 2^24 and a multiple of 8,
  *                  kv_head_stride >= capacity*kv_tok_stride)
  *   capacity       number of token positions per head in the caches
  *   active_off [host] [A] first cache position of each active chunk's slot, in causal

@@ -17,6 +17,7 @@ int check_kv_layout(const void* k_cache, const void* v_cache, int64_t head_strid
     if (bad_dtype(dtype) || H_k < 1 || positions < 1) return FC_INVALID_ARGUMENT;
     if (d != 64 && d != 128) return FC_UNSUPPORTED;
     if (tok_stride < d || head_stride < positions * tok_stride) return FC_INVALID_ARGUMENT;
+    if (tok_stride > (1 << 24)) return FC_UNSUPPORTED;   // kernels keep in-tile byte offsets in 32 bits
     const int per16 = 16 / esize(dtype);
     if (tok_stride % per16 != 0 || head_stride % per16 != 0) return FC_UNSUPPORTED;
     if (!aligned16(k_cache) || !aligned16(v_cache)) return FC_UNSUPPORTED;

@@ -92,6 +92,8 @@ def test_attend_rejects_bad_arguments(L):
     assert attend(L, ts=32) == INVALID                         # token stride < d
     assert attend(L, hs=100) == INVALID                        # head stride < capacity rows
     assert attend(L, ts=66, hs=768 * 66) == UNSUPPORTED        # rows not 16-byte aligned
+    big = (1 << 24) + 8
+    assert attend(L, ts=big, hs=768 * big) == UNSUPPORTED      # stride beyond the 32-bit tile offsets
     assert attend(L, off=(ctypes.c_int32 * 2)(512, 700)) == INVALID   # slot past capacity
     assert attend(L, off=(ctypes.c_int32 * 2)(512, 600)) == INVALID   # overlapping slots
     assert attend(L, off=(ctypes.c_int32 * 2)(400, 640)) == INVALID   # slot inside clean region
