@@ -78,7 +78,10 @@ def test_captured_step_replays_to_the_eager_bits():
         res_cache.zero_()
         g.replay()
         got = snapshot()
+        n_rows = int(holder["dec"]["n_recompute"].item()) * wl.L_c
         for i, (x, y) in enumerate(zip(got, ref)):
+            if i == 5:      # the row log-sum-exp is only written for the recomputed blocks
+                x, y = x[:, :n_rows], y[:, :n_rows]
             if x.is_floating_point():
                 assert torch.equal(torch.nan_to_num(x.float()), torch.nan_to_num(y.float())), (replay, i)
             else:
