@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C2", choices=["C2", "C3", "mid"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
-    ap.add_argument("--cpu-rows", type=int, default=256, help="oracle attention rows per chunk")
+    ap.add_argument("--cpu-rows", type=int, default=768, help="oracle attention rows per chunk")
     ap.add_argument("--qkv", default="normal", choices=["normal", "const"],
                     help="const: constant Q/K/V (same instruction stream, full clocks) -- shows how "
                          "much of the attention time is the power limit; not a valid bench result")
@@ -85,9 +85,9 @@ def cpu_baseline(wl, d, a, rows_per_chunk):
     t0 = time.perf_counter()
     O.chunk_decide(d["x_cur"], d["x_prev"], d["step_idx"], wl.warmup_m, 0.0, d["acc"])
     t_dec = time.perf_counter() - t0
-    mass = np.full((1, wl.L_k), 1.0 / wl.L_k, dtype=np.float32)
+    mass = np.full((wl.H_k, wl.L_k), 1.0 / wl.L_k, dtype=np.float32)
     t0 = time.perf_counter()
-    O.kv_compress(kc[:1, :wl.L_k], vc[:1, :wl.L_k], wl.L_k, wl.budget, mass, wl.pool_k, wl.lam)
+    O.kv_compress(kc[:, :wl.L_k], vc[:, :wl.L_k], wl.L_k, wl.budget, mass, wl.pool_k, wl.lam)
     t_cmp = time.perf_counter() - t0
     esz = 2 if wl.dtype == "bf16" else 4
     return {
@@ -96,9 +96,9 @@ def cpu_baseline(wl, d, a, rows_per_chunk):
                    f"({flops / 1e9:.1f} GFLOP in {t_att:.2f} s; whole tensor would take "
                    f"{wl.attention_flops() / (flops / t_att):.0f} s); change metric on the full "
                    f"tensors in {t_dec:.2f} s ({2 * wl.A * wl.chunk_elems * esz / t_dec / 1e9:.2f} GB/s); "
-                   f"compression of 1 of {wl.H_k} heads in {t_cmp:.2f} s "
-                   f"({compress_min_bytes(wl, wl.L_k, wl.budget) / wl.H_k / t_cmp / 1e9:.3f} GB/s)"),
-        "attention_s": t_att, "decide_s": t_dec, "compress_one_head_s": t_cmp,
+                   f"compression of all {wl.H_k} heads in {t_cmp:.2f} s "
+                   f"({compress_min_bytes(wl, wl.L_k, wl.budget) / t_cmp / 1e9:.3f} GB/s)"),
+        "attention_s": t_att, "decide_s": t_dec, "compress_s": t_cmp,
     }
 
 
