@@ -174,7 +174,7 @@ struct __attribute__((aligned(16))) MassSmem {
     __attribute__((aligned(16))) bf16_t q[kRowGroup][D + 8];
     union __attribute__((aligned(16))) {
         __attribute__((aligned(16))) bf16_t k[kTile][D + 8];
-        float merge[2][32][kTile + 1];   // per-lane (max, sum) of 32 rows, after the tile loop
+        float merge[2][32][17];          // (max, sum) partials of the rows, after the tile loop
     };
     float lse[kRowGroup];
     float acc[kSpan];
@@ -241,6 +241,31 @@ __device__ __forceinline__ void tile_scores(const MassSmem<D>& sm, int wave, int
     }
 }
 
+// S^T[key][row] for this wavefront's 32 keys of the tile and the 64 staged rows (the operands
+// of tile_scores swapped): st[rb][r] = key wave*32 + (r/4)*8 + (lane/32)*4 + r%4,
+// row rb*32 + lane%32 -- one observation row per lane, so its max and sum are in-lane.
+template <int D>
+__device__ __forceinline__ void tile_scores_t(const MassSmem<D>& sm, int wave, int lane,
+                                              f32x16_t (&st)[2]) {
+    const int n = lane & 31, half = lane >> 5;
+    bf16x8_t kf[D / 16];
+#pragma unroll
+    for (int kb = 0; kb < D / 16; ++kb)
+        kf[kb] = *reinterpret_cast<const bf16x8_t*>(&sm.k[wave * 32 + n][kb * 16 + half * 8]);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        f32x16_t c = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int kb = 0; kb < D / 16; ++kb) {
+            const bf16x8_t qf =
+                *reinterpret_cast<const bf16x8_t*>(&sm.q[rb * 32 + n][kb * 16 + half * 8]);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf, c, 0, 0, 0);
+        }
+        st[rb] = c;
+    }
+}
+
+// Pass 1: per observation row, max and sum of exp2 over this block's span of keys.
 template <int D>
 __global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, int nrg, int np,
                                                               float* __restrict__ pm,
@@ -251,6 +276,7 @@ __global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, i
     const int h = blockIdx.y;
     const int hk = h / (a.H_q / a.H_k);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 31, half = lane >> 5;
     const bf16_t* kh = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
     const int jb = blockIdx.x * kSpan;
     const int left = a.mass_len - jb;
@@ -265,65 +291,67 @@ __global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, i
     stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
     u32x4_native kr[D / 16];
     fetch_ktile<D>(a, kh, jb, kr);
-    float m[2][16], l[2][16];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { m[rb][r] = kNegBig; l[rb][r] = 0.f; }
+    float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};   // of row rb*32 + n over this lane's keys
     for (int t = 0; t < nt; ++t) {
         __syncthreads();
         store_ktile<D>(sm.k, kr);
         __syncthreads();
         fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);   // past the end: clamped, unused
-        f32x16_t s[2];
-        tile_scores<D>(sm, wave, lane, s);
-        const bool ok = jb + t * kTile + wave * 32 + (lane & 31) < a.mass_len;
+        f32x16_t st[2];
+        tile_scores_t<D>(sm, wave, lane, st);
+        const int key0 = jb + t * kTile + wave * 32 + half * 4;   // + (r/4)*8 + r%4
+        if (key0 - half * 4 + 32 <= a.mass_len) {     // all 32 keys of this wavefront are real
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+            for (int rb = 0; rb < 2; ++rb) {
+                float tm = st[rb][0];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float v = ok ? s[rb][r] * c2 : kNegBig;
-                const float mn = fmaxf(m[rb][r], v);
-                const float e = ok ? __builtin_amdgcn_exp2f(v - mn) : 0.f;
-                l[rb][r] = l[rb][r] * __builtin_amdgcn_exp2f(m[rb][r] - mn) + e;
-                m[rb][r] = mn;
+                for (int r = 1; r < 16; ++r) tm = fmaxf(tm, st[rb][r]);
+                const float mn = fmaxf(m[rb], tm * c2);
+                float acc = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc += __builtin_amdgcn_exp2f(fmaf(st[rb][r], c2, -mn));
+                l[rb] = fmaf(l[rb], __builtin_amdgcn_exp2f(m[rb] - mn), acc);
+                m[rb] = mn;
             }
+        } else {                                      // the ragged end of the scored range
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                float tm = kNegBig;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (key0 + (r >> 2) * 8 + (r & 3) < a.mass_len) tm = fmaxf(tm, st[rb][r] * c2);
+                const float mn = fmaxf(m[rb], tm);
+                float acc = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (key0 + (r >> 2) * 8 + (r & 3) < a.mass_len)
+                        acc += __builtin_amdgcn_exp2f(fmaf(st[rb][r], c2, -mn));
+                // no real key yet (m and mn both at the floor): keep l = 0
+                l[rb] = (mn > kNegBig) ? fmaf(l[rb], __builtin_amdgcn_exp2f(m[rb] - mn), acc) : 0.f;
+                m[rb] = mn;
+            }
+        }
     }
-    // merge the 128 per-lane statistics of every row, in a fixed order
-    const int col = wave * 32 + (lane & 31);
+    // merge the 8 partials of every row (4 wavefronts x 2 lane halves), in a fixed order
+    __syncthreads();
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-            sm.merge[0][row][col] = m[rb][r];
-            sm.merge[1][row][col] = l[rb][r];
-        }
-        __syncthreads();
-        const int row = tid >> 3, part = tid & 7;
+        sm.merge[0][rb * 16 + (n >> 1)][(n & 1) * 8 + wave * 2 + half] = m[rb];
+        sm.merge[1][rb * 16 + (n >> 1)][(n & 1) * 8 + wave * 2 + half] = l[rb];
+    }
+    __syncthreads();
+    if (tid < kRowGroup) {
+        const int q = tid;   // rb*32 + n
+        const float* mp = &sm.merge[0][(q >> 5) * 16 + ((q & 31) >> 1)][(q & 1) * 8];
+        const float* lp = &sm.merge[1][(q >> 5) * 16 + ((q & 31) >> 1)][(q & 1) * 8];
         float mx = kNegBig;
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sm.merge[0][row][part * 16 + i]);
-        float sum = 0.f;
-        for (int i = 0; i < 16; ++i)
-            sum += sm.merge[1][row][part * 16 + i] *
-                   __builtin_amdgcn_exp2f(sm.merge[0][row][part * 16 + i] - mx);
 #pragma unroll
-        for (int o = 1; o < 8; o <<= 1) {
-            const float mo = __shfl_xor(mx, o, FC_WAVE), so = __shfl_xor(sum, o, FC_WAVE);
-            const float mn = fmaxf(mx, mo);
-            // the lower lane's term first on both sides, so partners agree bit for bit
-            const float lo = (part & o) ? so * __builtin_amdgcn_exp2f(mo - mn)
-                                        : sum * __builtin_amdgcn_exp2f(mx - mn);
-            const float hi = (part & o) ? sum * __builtin_amdgcn_exp2f(mx - mn)
-                                        : so * __builtin_amdgcn_exp2f(mo - mn);
-            sum = lo + hi;
-            mx = mn;
-        }
-        if (part == 0) {
-            pm[(((int64_t)h * nrg + rg) * kRowGroup + rb * 32 + row) * np + blockIdx.x] = mx;
-            pl[(((int64_t)h * nrg + rg) * kRowGroup + rb * 32 + row) * np + blockIdx.x] = sum;
-        }
+        for (int i = 0; i < 8; ++i) mx = fmaxf(mx, mp[i]);
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum += lp[i] * __builtin_amdgcn_exp2f(mp[i] - mx);
+        pm[(((int64_t)h * nrg + rg) * kRowGroup + q) * np + blockIdx.x] = mx;
+        pl[(((int64_t)h * nrg + rg) * kRowGroup + q) * np + blockIdx.x] = sum;
     }
     }   // row groups
 }

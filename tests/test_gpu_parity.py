@@ -238,6 +238,7 @@ def test_malformed_recompute_list_is_skipped_not_followed(wl):
 @pytest.mark.parametrize("dtype,d,A,L_c,L_clean", [
     ("bf16", 128, 1, 1, 0), ("bf16", 128, 2, 1, 1), ("bf16", 64, 3, 33, 63), ("bf16", 128, 2, 257, 64),
     ("bf16", 128, 1, 64, 65), ("bf16", 128, 4, 31, 0), ("f32", 64, 2, 1, 1), ("f32", 128, 1, 65, 0),
+    ("bf16", 128, 16, 20, 30), ("f32", 64, 16, 9, 0),      # the largest window the ABI allows
 ])
 def test_attend_edge_sizes(dtype, d, A, L_c, L_clean):
     """One-row chunks, chunks and clean regions one short of / equal to / one past a 64-key tile
