@@ -7,11 +7,13 @@
 // Two passes over the keys (the softmax normaliser of a row is known only after all keys):
 //   stats  per-row running (max, sum-exp) per block of keys             -> partials
 //   cols   per key: sum over rows of exp2(s - lse), fixed order         -> mass
-// bf16: both passes form S = Q K^T with v_mfma_f32_32x32x16_bf16 on 128-key tiles staged
-// through LDS by coalesced 16-byte loads (the passes are bound by the two reads of K);
-// the accumulator layout puts one key per lane and the 64 (padded) rows in registers, so
-// the per-key sum over rows is in-lane and the per-row statistics are kept per lane and
-// merged once per block.  fp32: one thread per key with its key in registers, fp32 FMA.
+// bf16: both passes use v_mfma_f32_32x32x16_bf16 on 128-key tiles staged through LDS by
+// coalesced 16-byte loads (the passes are bound by the two reads of K), each in the
+// orientation that makes its reduction in-lane: stats forms S^T = K Q^T (one row per lane,
+// its keys in registers: the row's max and sum need no exchange, 8 partials per row are
+// merged once per block); cols forms S = Q K^T (one key per lane, the 64 padded rows in
+// registers: the key's sum over rows is in-lane).  fp32: one thread per key with its key in
+// registers, fp32 FMA.
 // Rows are processed in groups of at most 64; groups accumulate into mass in launch
 // order, so the result is deterministic.  No atomics.
 #include "fc_common.hpp"
