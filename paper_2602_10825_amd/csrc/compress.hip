@@ -63,13 +63,35 @@ struct Slice {
     }
 };
 
-// all-reduce over the 16 lanes of a group; every lane ends with identical bits
-__device__ __forceinline__ double group_sum(double v) {
-    v += __shfl_xor(v, 1, 16);
-    v += __shfl_xor(v, 2, 16);
-    v += __shfl_xor(v, 4, 16);
-    v += __shfl_xor(v, 8, 16);
-    return v;
+// Sixteen sums over the 16 lanes of a group, one wanted per lane (lane u wants the sum of
+// v[u]): in the step for lane bit b a lane keeps the half of its values whose index has bit b
+// like its own, hands the other half to its partner and adds what it receives -- 15 exchanges
+// instead of the 64 of sixteen all-reduces.  Every sum is added up along the same tree over
+// the lanes (bit 1, 2, 4, 8), so its bits do not depend on which token it belongs to.
+__device__ __forceinline__ double group_sum_scatter(double (&v)[16], int u) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {    // lane bit 1 <-> value index bit 1: pairs (2i, 2i+1)
+        const bool up = u & 1;
+        const double keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
+        v[i] = keep + __shfl_xor(give, 1, 16);          // v[i] now belongs to index 2i + (u&1)
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {    // bit 2: indices 4i + (u&1) and 4i + 2 + (u&1)
+        const bool up = u & 2;
+        const double keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
+        v[i] = keep + __shfl_xor(give, 2, 16);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {    // bit 4
+        const bool up = u & 4;
+        const double keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
+        v[i] = keep + __shfl_xor(give, 4, 16);
+    }
+    {                                // bit 8
+        const bool up = u & 8;
+        const double keep = up ? v[1] : v[0], give = up ? v[0] : v[1];
+        return keep + __shfl_xor(give, 8, 16);
+    }
 }
 
 // A group of 16 lanes takes 16 consecutive tokens per round: all 16 row slices are loaded
@@ -95,7 +117,7 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
             const int j = j0 + i;
             raw[i] = S::load(base + (int64_t)(j < L ? j : L - 1) * tok_stride, u);
         }
-        double mine = 0.0;
+        double part[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             double x[EL];
@@ -103,9 +125,9 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
             double n2 = 0.0;
 #pragma unroll
             for (int e = 0; e < EL; ++e) n2 = fma(x[e], x[e], n2);
-            n2 = group_sum(n2);
-            mine = (i == u) ? n2 : mine;
+            part[i] = n2;
         }
+        const double mine = group_sum_scatter(part, u);
         const double inv_mine = 1.0 / fmax(sqrt(mine), 1e-12);
         if (j0 + u < L) tokinfo[(int64_t)h * L + j0 + u] = make_double2(inv_mine, (mine * inv_mine) * inv_mine);
 #pragma unroll
@@ -183,7 +205,7 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
         }
         const bool have = j0 + u < L;
         const double2 ti = tokinfo[(int64_t)h * L + (have ? j0 + u : L - 1)];
-        double mine = 0.0;
+        double part[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             double x[EL];
@@ -191,9 +213,9 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
             double dot = 0.0;
 #pragma unroll
             for (int e = 0; e < EL; ++e) dot = fma(x[e], s[e], dot);
-            dot = group_sum(dot);
-            mine = (i == u) ? dot : mine;
+            part[i] = dot;
         }
+        const double mine = group_sum_scatter(part, u);
         if (have) {
             const double ej = exp((mine * ti.x - ti.y) / dL);
             e_out[(int64_t)h * L + j0 + u] = ej;
@@ -435,7 +457,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __shared__ uint32_t hist[kBins];
     __shared__ uint64_t cand[kCand];
     __shared__ uint32_t wtot[kSelThreads / FC_WAVE];
-    __shared__ uint64_t sh_prefix;
+    __shared__ uint64_t sh_prefix, sh_thr;
     __shared__ uint32_t sh_need, sh_count, sh_ncand;
 
     uint64_t kmin, kmax;
@@ -508,6 +530,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
                 __syncthreads();
                 ncand = sh_ncand;
                 in_lds = true;
+            }
+            // one candidate left in the chosen bin: it is the threshold, whatever its low bits
+            if (in_lds && rem > 0 && sh_count == 1u) {
+                const uint64_t hm = ~0ull << rem;
+                for (uint32_t i = tid; i < ncand; i += kSelThreads)
+                    if ((cand[i] & hm) == prefix) sh_thr = cand[i];
+                __syncthreads();
+                prefix = sh_thr;
+                rem = 0;
             }
         }
         thr = prefix;
