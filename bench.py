@@ -9,7 +9,15 @@ SkyReels-V2-1.3B-like single-layer shape (12 heads x 128, 2 active chunks of 102
     flowcache_scatter_kv     new K/V of the recompute chunks into their cache slots
     flowcache_attend         chunk-causal bf16 attention (all chunks recompute: eps = 0)
     flowcache_attention_mass importance of the first L_k cache positions (50 observation rows)
-    flowcache_kv_compress    scoring, top-B selection, compaction (fresh cache copy per step)
+    flowcache_kv_select      scoring and top-B selection  } together = flowcache_kv_compress
+    flowcache_kv_compact     in-place compaction          } (fresh cache copy per step)
+
+The calls run back to back on one stream.  The importance mass and the selection only read K,
+so with ``--overlap`` the step runs them on a second HIP stream beside the attention kernel
+(they fit into the partly empty last round of its launch) and the compaction, which overwrites
+K and V, waits for both: about 1 % more steps per second on C2, at the price of an attention
+kernel that is itself about 1 % slower, so it is not the default.  After the timed region a
+few sequential steps give every call's duration alone (``stage_ms_alone``).
 
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
@@ -45,6 +53,8 @@ def parse():
     ap.add_argument("--workload", default="C2", choices=["C2", "C3", "mid"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
     ap.add_argument("--cpu-rows", type=int, default=768, help="oracle attention rows per chunk")
+    ap.add_argument("--overlap", action="store_true",
+                    help="two streams: mass and selection beside the attention instead of after it")
     ap.add_argument("--qkv", default="normal", choices=["normal", "const"],
                     help="const: constant Q/K/V (same instruction stream, full clocks) -- shows how "
                          "much of the attention time is the power limit; not a valid bench result")
@@ -165,7 +175,8 @@ def main():
     wl = {"C2": synth.C2, "C3": synth.C3, "mid": synth.MID_BF16}[args.workload]
     dev = "cuda"
     K, W = args.steps, args.warmup
-    nset = K + W
+    K_ALONE = 5     # sequential steps after the timed region: every call's duration alone
+    nset = K + W + K_ALONE + 1
 
     # ---- synthetic inputs, resident in HBM before the timed region -------------------
     d = synth.decide_inputs(wl, seed=0)
@@ -201,9 +212,13 @@ def main():
     q_obs = q[wl.A * wl.L_c - Wobs:]          # last W rows of the last active chunk
 
     names = ["decide", "scatter", "attend", "mass", "compress"]
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(K)]
+    main_stream = torch.cuda.current_stream()
+    side_stream = torch.cuda.Stream()          # default priority
 
-    def step(i, events=None):
+    def new_events(n):
+        return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+    def step_sequential(i, events=None):
         s = i % NDEC
         if events: events[0].record()
         dec = B.flowcache_chunk_decide(x_cur[s], x_prev[s], step_idx, wl.warmup_m, 0.0, acc,
@@ -223,6 +238,41 @@ def main():
         if events: events[5].record()
         return dec
 
+    def step_overlapped(i, events=None):
+        """events: 0-3 decide / scatter / attend on the main stream, 4-5 around the compaction,
+        6-8 mass / selection on the side stream."""
+        s = i % NDEC
+        if events: events[0].record()
+        dec = B.flowcache_chunk_decide(x_cur[s], x_prev[s], step_idx, wl.warmup_m, 0.0, acc,
+                                       x_compact=x_compact, workspace=ws_dec)
+        if events: events[1].record()
+        B.flowcache_scatter_kv(k_new, v_new, k_sets[i], v_sets[i], wl.L_c, wl.L_clean, active_off,
+                               dec["recompute_idx"], dec["n_recompute"])
+        if events: events[2].record()
+        fork = torch.cuda.Event()
+        fork.record(main_stream)
+        with torch.cuda.stream(side_stream):       # K is final after the scatter: read-only work
+            side_stream.wait_event(fork)
+            if events: events[6].record(side_stream)
+            mass = B.flowcache_attention_mass(q_obs, k_sets[i], L_k, workspace=ws_mass)
+            if events: events[7].record(side_stream)
+            B.flowcache_kv_select(k_sets[i], L_k, budget, mass, wl.pool_k, wl.lam, kept_idx=kept,
+                                  workspace=ws_cmp)
+            if events: events[8].record(side_stream)
+            join = torch.cuda.Event()
+            join.record(side_stream)
+        B.flowcache_attend(q, None, None, k_sets[i], v_sets[i], wl.L_c, wl.L_clean, active_off,
+                           dec["recompute_idx"], dec["n_recompute"], out=out, want_lse=False,
+                           workspace=ws_att)
+        if events: events[3].record()
+        main_stream.wait_event(join)               # the compaction overwrites what both read
+        if events: events[4].record()
+        B.flowcache_kv_compact(k_sets[i], v_sets[i], L_k, budget, kept, workspace=ws_cmp)
+        if events: events[5].record()
+        return dec
+
+    step = step_overlapped if args.overlap else step_sequential
+    ev = [new_events(9) for _ in range(K)]
     for i in range(W):
         step(i)
     torch.cuda.synchronize()
@@ -233,20 +283,35 @@ def main():
     wall = time.perf_counter() - t0
     assert int(dec["n_recompute"].item()) == wl.A, "eps = 0 must recompute every chunk"
 
-    stage_ms = {n: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K)]))
-                for j, n in enumerate(names)}
+    def mean_ms(evs, j0, j1):
+        return float(np.mean([e[j0].elapsed_time(e[j1]) for e in evs]))
+
+    if not args.overlap:
+        stage_ms = {n: mean_ms(ev, j, j + 1) for j, n in enumerate(names)}
+    else:
+        stage_ms = {"decide": mean_ms(ev, 0, 1), "scatter": mean_ms(ev, 1, 2), "attend": mean_ms(ev, 2, 3),
+                    "mass (side stream, beside attend)": mean_ms(ev, 6, 7),
+                    "select (side stream, beside attend)": mean_ms(ev, 7, 8),
+                    "compact": mean_ms(ev, 4, 5)}
+    # every call alone: a few sequential steps outside the timed region
+    ev_alone = [new_events(6) for _ in range(K_ALONE)]
+    step_sequential(W + K)
+    for i in range(K_ALONE):
+        step_sequential(W + K + 1 + i, ev_alone[i])
+    torch.cuda.synchronize()
+    stage_alone = {n: mean_ms(ev_alone, j, j + 1) for j, n in enumerate(names)}
     ms_per_step = wall * 1e3 / K
     flops = float(wl.attention_flops())
     esz = 2 if wl.dtype == "bf16" else 4
-    att_tflops = flops / (stage_ms["attend"] * 1e-3) / 1e12
+    att_tflops = flops / (stage_ms["attend"] * 1e-3) / 1e12      # in the timed region
     dec_bytes = 2 * wl.A * wl.chunk_elems * esz + 2 * wl.A * wl.chunk_elems * esz   # metric + gather r/w
     cmp_bytes = compress_min_bytes(wl, L_k, budget)
     sc_bytes = 2 * 2 * wl.A * wl.L_c * wl.H_k * wl.d * esz
     mass_bytes = 2 * wl.H_k * L_k * wl.d * esz
 
     def hbm(name, nbytes):
-        g = nbytes / (stage_ms[name] * 1e-3) / 1e9
-        return {"call": name, "bound": "hbm", "algorithmic_bytes": int(nbytes), "ms": stage_ms[name],
+        g = nbytes / (stage_alone[name] * 1e-3) / 1e9
+        return {"call": name, "bound": "hbm", "algorithmic_bytes": int(nbytes), "ms": stage_alone[name],
                 "achieved": g, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": g / PEAK_HBM_GBPS}
 
     result = {
@@ -266,10 +331,13 @@ def main():
                      "ms": stage_ms["attend"],
                      "note": "a loop of nothing but bf16 MFMAs on random operands sustains 1330-1410 "
                              "TFLOP/s on this chip (power-limited; profiles/peaks_measured.md)"},
-        "kv_compress_GBps": cmp_bytes / (stage_ms["compress"] * 1e-3) / 1e9,
+        "kv_compress_GBps": cmp_bytes / (stage_alone["compress"] * 1e-3) / 1e9,
         "calls": [hbm("decide", dec_bytes), hbm("scatter", sc_bytes), hbm("mass", mass_bytes),
                   hbm("compress", cmp_bytes)],
         "stage_ms": stage_ms,
+        "stage_ms_alone": stage_alone,
+        "streams": "one" if not args.overlap else
+                   "two: mass and selection run beside the attention kernel, the compaction after both",
     }
     result["widened_rows"] = widened_rows(wl, B, x_cur, x_prev, x_compact, step_idx, dec, q, k_sets[0],
                                           ws_dec, L_k)

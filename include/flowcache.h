@@ -22,6 +22,7 @@
  *   flowcache_attention_mass  the importance mass alone, for explicit observation queries
  *                             (Sec. 3.3, Eq. (9); observation window of App. C.2).
  *   flowcache_kv_compress_grouped  the same at frame / chunk key granularity (App. D.2.1).
+ *   flowcache_kv_select, flowcache_kv_compact  the two halves of flowcache_kv_compress.
  *   flowcache_kv_compress     joint importance-redundancy scoring, per-head top-B selection
  *                             and in-place compaction of K and V (Sec. 3.3, Eq. (10)-(12),
  *                             linear-time redundancy of App. C.2, phases of App. C.1).
@@ -257,6 +258,30 @@ int flowcache_kv_compress(void* k_cache, void* v_cache, int64_t kv_head_stride,
                           int32_t* kept_idx, void* workspace, size_t workspace_bytes,
                           fc_stream stream);
 size_t flowcache_kv_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype);
+
+/*
+ * The two halves of flowcache_kv_compress as calls of their own, for callers that overlap the
+ * scoring and selection (which only read K) with other work on another stream -- the
+ * attention of the same tick, say -- and move the rows afterwards.  Same arguments, same
+ * workspace size (flowcache_kv_compress_workspace) and same results: select followed by
+ * compact leaves kept_idx, K and V bit-identical to one flowcache_kv_compress call
+ * (Sec. 3.3, Eq. (10)-(12) for the first; the in-place compaction for the second).
+ *
+ *   flowcache_kv_select   writes kept_idx [H_k, min(budget, L_k)]; K is not modified
+ *   flowcache_kv_compact  moves row kept_idx[h][i] of K and V to position i, for i < budget
+ *                         (nothing moves when budget >= L_k).  kept_idx [dev] must be
+ *                         ascending per head, as written by flowcache_kv_select; entries
+ *                         outside [0, L_k) are skipped.  The status word of
+ *                         flowcache_kv_compress_status_offset applies to this call too.
+ */
+int flowcache_kv_select(const void* k_cache, int64_t kv_head_stride, int64_t kv_tok_stride,
+                        fc_dtype dtype, int H_k, int d, int L_k, int budget, const float* mass,
+                        int pool_k, double lambda, int32_t* kept_idx, void* workspace,
+                        size_t workspace_bytes, fc_stream stream);
+int flowcache_kv_compact(void* k_cache, void* v_cache, int64_t kv_head_stride,
+                         int64_t kv_tok_stride, fc_dtype dtype, int H_k, int d, int L_k,
+                         int budget, const int32_t* kept_idx, void* workspace,
+                         size_t workspace_bytes, fc_stream stream);
 
 /*
  * The same compression with keys scored and kept at a coarser granularity (the frame- and

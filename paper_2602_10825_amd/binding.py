@@ -29,6 +29,7 @@ EXPORTS = (
     "flowcache_attend", "flowcache_attend_workspace", "flowcache_scatter_kv",
     "flowcache_attention_mass", "flowcache_attention_mass_workspace",
     "flowcache_kv_compress", "flowcache_kv_compress_workspace",
+    "flowcache_kv_select", "flowcache_kv_compact",
     "flowcache_kv_compress_grouped", "flowcache_kv_compress_grouped_workspace",
     "flowcache_kv_compress_status_offset",
     "flowcache_sched_state_bytes", "flowcache_sched_init", "flowcache_sched_capacity",
@@ -88,6 +89,12 @@ def lib() -> ctypes.CDLL:
     L.flowcache_kv_compress.restype = c_int
     L.flowcache_kv_compress.argtypes = [c_vp, c_vp, c_i64, c_i64, c_int, c_int, c_int, c_int, c_int,
                                         c_vp, c_int, c_d, c_vp, c_vp, c_sz, c_vp]
+    L.flowcache_kv_select.restype = c_int
+    L.flowcache_kv_select.argtypes = [c_vp, c_i64, c_i64, c_int, c_int, c_int, c_int, c_int, c_vp, c_int,
+                                      c_d, c_vp, c_vp, c_sz, c_vp]
+    L.flowcache_kv_compact.restype = c_int
+    L.flowcache_kv_compact.argtypes = [c_vp, c_vp, c_i64, c_i64, c_int, c_int, c_int, c_int, c_int, c_vp,
+                                       c_vp, c_sz, c_vp]
     L.flowcache_kv_compress_grouped_workspace.restype = c_sz
     L.flowcache_kv_compress_grouped_workspace.argtypes = [c_int] * 6
     L.flowcache_kv_compress_grouped.restype = c_int
@@ -310,6 +317,47 @@ def flowcache_kv_compress(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int
                                  _stream(stream))
     _check("flowcache_kv_compress", st)
     return kept_idx
+
+
+def flowcache_kv_select(k_cache: torch.Tensor, L_k: int, budget: int, mass: torch.Tensor,
+                        pool_k: int = 7, lam: float = 0.07, kept_idx: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Scoring and selection only: returns kept_idx ``[H_k, min(budget, L_k)]``; K is not modified."""
+    H_k, capacity, d = k_cache.shape
+    dev = k_cache.device
+    assert k_cache.stride(2) == 1 and L_k <= capacity
+    assert mass.dtype == torch.float32 and mass.is_contiguous() and mass.shape == (H_k, L_k)
+    nkeep = min(budget, L_k)
+    if kept_idx is None:
+        kept_idx = torch.empty((H_k, nkeep), dtype=torch.int32, device=dev)
+    L = lib()
+    code = _dtype_code(k_cache)
+    if workspace is None:
+        workspace = _workspace(L.flowcache_kv_compress_workspace(H_k, L_k, d, budget, code), dev)
+    st = L.flowcache_kv_select(_ptr(k_cache), k_cache.stride(0), k_cache.stride(1), code, H_k, d,
+                               int(L_k), int(budget), _ptr(mass), int(pool_k), float(lam),
+                               _ptr(kept_idx), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check("flowcache_kv_select", st)
+    return kept_idx
+
+
+def flowcache_kv_compact(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int, budget: int,
+                         kept_idx: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                         stream=None) -> None:
+    """Moves row ``kept_idx[h][i]`` of K and V to position i, in place."""
+    H_k, capacity, d = k_cache.shape
+    dev = k_cache.device
+    assert k_cache.stride(2) == 1 and v_cache.stride() == k_cache.stride() and L_k <= capacity
+    assert kept_idx.dtype == torch.int32 and kept_idx.is_contiguous()
+    assert kept_idx.shape == (H_k, min(budget, L_k))
+    L = lib()
+    code = _dtype_code(k_cache)
+    if workspace is None:
+        workspace = _workspace(L.flowcache_kv_compress_workspace(H_k, L_k, d, budget, code), dev)
+    st = L.flowcache_kv_compact(_ptr(k_cache), _ptr(v_cache), k_cache.stride(0), k_cache.stride(1),
+                                code, H_k, d, int(L_k), int(budget), _ptr(kept_idx), _ptr(workspace),
+                                workspace.numel(), _stream(stream))
+    _check("flowcache_kv_compact", st)
 
 
 def flowcache_kv_compress_grouped(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int, budget: int,

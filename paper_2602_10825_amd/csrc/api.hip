@@ -264,7 +264,7 @@ int flowcache_kv_compress_grouped(void* k_cache, void* v_cache, int64_t kv_head_
     if (workspace_bytes < flowcache_kv_compress_grouped_workspace(H_k, L_k, d, budget, group, dtype))
         return FC_WORKSPACE_TOO_SMALL;
     FcCompressArgs c{k_cache, v_cache, kv_head_stride, kv_tok_stride, dtype, H_k, d, L_k, budget,
-                     mass, pool_k, lambda, kept_idx, workspace, group};
+                     mass, pool_k, lambda, kept_idx, workspace, group, 0};
     return fc_launch_compress(c, (hipStream_t)stream);
 }
 
@@ -295,7 +295,41 @@ int flowcache_kv_compress(void* k_cache, void* v_cache, int64_t kv_head_stride,
     if (workspace_bytes < fc_compress_workspace(H_k, L_k, d, budget, dtype))
         return FC_WORKSPACE_TOO_SMALL;
     FcCompressArgs c{k_cache, v_cache, kv_head_stride, kv_tok_stride, dtype, H_k, d, L_k, budget,
-                     mass, pool_k, lambda, kept_idx, workspace, 1};
+                     mass, pool_k, lambda, kept_idx, workspace, 1, 0};
+    return fc_launch_compress(c, (hipStream_t)stream);
+}
+
+int flowcache_kv_select(const void* k_cache, int64_t kv_head_stride, int64_t kv_tok_stride,
+                        fc_dtype dtype, int H_k, int d, int L_k, int budget, const float* mass,
+                        int pool_k, double lambda, int32_t* kept_idx, void* workspace,
+                        size_t workspace_bytes, fc_stream stream) {
+    if (!mass || !kept_idx || !workspace) return FC_INVALID_ARGUMENT;
+    if (L_k < 1 || budget < 1) return FC_INVALID_ARGUMENT;
+    if (pool_k < 1 || pool_k % 2 == 0) return FC_INVALID_ARGUMENT;
+    if (!(lambda >= 0.0 && lambda <= 1.0)) return FC_INVALID_ARGUMENT;
+    int st = check_kv_layout(k_cache, k_cache, kv_head_stride, kv_tok_stride, L_k, dtype, H_k, d);
+    if (st != FC_OK) return st;
+    if (workspace_bytes < fc_compress_workspace(H_k, L_k, d, budget, dtype))
+        return FC_WORKSPACE_TOO_SMALL;
+    // the selection phase only reads K
+    FcCompressArgs c{const_cast<void*>(k_cache), const_cast<void*>(k_cache), kv_head_stride,
+                     kv_tok_stride, dtype, H_k, d, L_k, budget, mass, pool_k, lambda, kept_idx,
+                     workspace, 1, 1};
+    return fc_launch_compress(c, (hipStream_t)stream);
+}
+
+int flowcache_kv_compact(void* k_cache, void* v_cache, int64_t kv_head_stride,
+                         int64_t kv_tok_stride, fc_dtype dtype, int H_k, int d, int L_k,
+                         int budget, const int32_t* kept_idx, void* workspace,
+                         size_t workspace_bytes, fc_stream stream) {
+    if (!kept_idx || !workspace) return FC_INVALID_ARGUMENT;
+    if (L_k < 1 || budget < 1) return FC_INVALID_ARGUMENT;
+    int st = check_kv_layout(k_cache, v_cache, kv_head_stride, kv_tok_stride, L_k, dtype, H_k, d);
+    if (st != FC_OK) return st;
+    if (workspace_bytes < fc_compress_workspace(H_k, L_k, d, budget, dtype))
+        return FC_WORKSPACE_TOO_SMALL;
+    FcCompressArgs c{k_cache, v_cache, kv_head_stride, kv_tok_stride, dtype, H_k, d, L_k, budget,
+                     nullptr, 1, 0.0, const_cast<int32_t*>(kept_idx), workspace, 1, 2};
     return fc_launch_compress(c, (hipStream_t)stream);
 }
 

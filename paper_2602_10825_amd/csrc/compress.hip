@@ -691,6 +691,14 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(
     }
 }
 
+// the ticket / flag words compact_rows starts from, for a call that moves rows only
+__global__ __launch_bounds__(kThreads) void reset_sync_kernel(uint32_t* __restrict__ sync, int H, int ntile) {
+    const int h = blockIdx.x;
+    for (int i = threadIdx.x; i < ntile; i += kThreads) sync[64 * (H + 1) + (int64_t)h * ntile + i] = 0u;
+    if (threadIdx.x == 0) sync[64 * (h + 1)] = 0u;
+    if (h == 0 && threadIdx.x == 0) sync[0] = 0u;
+}
+
 struct WsLayout {
     size_t tokinfo, e, keys, psum, ssum, pz, pminmax, hist, sel, sync, total;
     int nblk, nb2, ntile;
@@ -725,6 +733,17 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
 template <typename T, int D>
 int launch_typed(const FcCompressArgs& a, hipStream_t s, bool compact = true) {
     const WsLayout w = layout(a.H_k, a.L_k, a.d, a.budget, a.dtype);
+    if (a.phase == 2) {   // rows only: the kept list is the caller's
+        uint32_t* sync2 = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(a.ws) + w.sync);
+        reset_sync_kernel<<<a.H_k, kThreads, 0, s>>>(sync2, a.H_k, w.ntile);
+        FC_LAUNCH_CHECK();
+        constexpr int VPR2 = D * (int)sizeof(T) / 16;
+        const int64_t hs2 = a.head_stride * (int64_t)sizeof(T) / 16, ts2 = a.tok_stride * (int64_t)sizeof(T) / 16;
+        compact_rows_kernel<VPR2><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
+            (uint4*)a.k_cache, (uint4*)a.v_cache, hs2, ts2, a.H_k, a.L_k, a.budget, w.ntile, a.kept, sync2);
+        FC_LAUNCH_CHECK();
+        return FC_OK;
+    }
     char* ws = reinterpret_cast<char*>(a.ws);
     double2* tokinfo = reinterpret_cast<double2*>(ws + w.tokinfo);
     double* e = reinterpret_cast<double*>(ws + w.e);
@@ -755,7 +774,7 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s, bool compact = true) {
     FC_LAUNCH_CHECK();
     write_kept_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, sel, a.L_k, a.budget, a.kept);
     FC_LAUNCH_CHECK();
-    if (!compact) return FC_OK;   // scoring and selection only (the grouped variant moves rows itself)
+    if (!compact || a.phase == 1) return FC_OK;   // scoring and selection only
     constexpr int VPR = D * (int)sizeof(T) / 16;
     const int64_t hs = a.head_stride * (int64_t)sizeof(T) / 16, ts = a.tok_stride * (int64_t)sizeof(T) / 16;
     compact_rows_kernel<VPR><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
@@ -888,6 +907,7 @@ size_t fc_compress_workspace(int H_k, int L_k, int d, int budget, fc_dtype dtype
 
 int fc_launch_compress(const FcCompressArgs& a, hipStream_t s) {
     if (a.budget >= a.L_k) {  // cache-filling phase: nothing to drop
+        if (a.phase == 2) return FC_OK;   // every row is already in place
         const int64_t n = (int64_t)a.H_k * a.L_k;
         iota_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(a.kept, a.H_k, a.L_k);
         FC_LAUNCH_CHECK();

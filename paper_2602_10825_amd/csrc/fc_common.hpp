@@ -137,6 +137,7 @@ struct FcCompressArgs {
     int H_k; int d; int L_k; int budget; const float* mass; int pool_k; double lambda;
     int32_t* kept; void* ws;
     int group;   // > 1: keys scored and kept in groups of this many consecutive tokens
+    int phase;   // 0: score, select and move rows; 1: score and select only; 2: move rows only
 };
 size_t fc_compress_grouped_workspace(int H_k, int L_k, int d, int budget, int group);
 size_t fc_compress_status_offset(int H_k, int L_k, int d, int budget, int group, fc_dtype dtype);

@@ -193,3 +193,27 @@ def test_grouped_compress_rejects_bad_arguments(L):
     assert L.flowcache_kv_compress_grouped_workspace(2, 1000, 128, 500, 30, 1) == 0
     assert L.flowcache_kv_compress_grouped_workspace(2, 1000, 128, 500, 1, 1) == \
         L.flowcache_kv_compress_workspace(2, 1000, 128, 500, 1)
+
+
+def test_kv_select_and_compact_reject_bad_arguments(L):
+    def sel(**kw):
+        a = dict(kc=P, hs=1024 * 128, ts=128, dtype=1, H=2, d=128, L_k=1000, budget=500, mass=P, pool=7,
+                 lam=0.07, kept=P, ws=P, wsb=1 << 26, stream=NULL)
+        a.update(kw)
+        return L.flowcache_kv_select(a["kc"], a["hs"], a["ts"], a["dtype"], a["H"], a["d"], a["L_k"],
+                                     a["budget"], a["mass"], a["pool"], a["lam"], a["kept"], a["ws"],
+                                     a["wsb"], a["stream"])
+
+    def cpt(**kw):
+        a = dict(kc=P, vc=P, hs=1024 * 128, ts=128, dtype=1, H=2, d=128, L_k=1000, budget=500, kept=P,
+                 ws=P, wsb=1 << 26, stream=NULL)
+        a.update(kw)
+        return L.flowcache_kv_compact(a["kc"], a["vc"], a["hs"], a["ts"], a["dtype"], a["H"], a["d"],
+                                      a["L_k"], a["budget"], a["kept"], a["ws"], a["wsb"], a["stream"])
+
+    assert sel(kc=NULL) == INVALID and sel(mass=NULL) == INVALID and sel(kept=NULL) == INVALID
+    assert sel(pool=2) == INVALID and sel(lam=-0.1) == INVALID and sel(budget=0) == INVALID
+    assert sel(d=96) == UNSUPPORTED and sel(wsb=64) == WS_SMALL and sel(ts=64) == INVALID
+    assert cpt(kc=NULL) == INVALID and cpt(vc=NULL) == INVALID and cpt(kept=NULL) == INVALID
+    assert cpt(L_k=0) == INVALID and cpt(budget=0) == INVALID
+    assert cpt(d=96) == UNSUPPORTED and cpt(wsb=64) == WS_SMALL and cpt(hs=100) == INVALID

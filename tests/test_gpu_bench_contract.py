@@ -29,6 +29,16 @@ def test_bench_json_contract():
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and isinstance(c["sample"], str)
     assert d["value"] > 0 and d["ms_per_step"] > 0
+    assert set(d["stage_ms_alone"]) == {"decide", "scatter", "attend", "mass", "compress"}
+    assert d["streams"] == "one" and set(d["stage_ms"]) == {"decide", "scatter", "attend", "mass", "compress"}
+
+
+def test_bench_overlap_mode_runs_mass_and_selection_on_a_second_stream():
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "mid", "--steps", "2",
+                          "--warmup", "1", "--no-cpu", "--overlap"], capture_output=True, text=True, cwd=ROOT)
+    assert res.returncode == 0, res.stderr[-2000:]
+    d = json.loads(res.stdout.strip().splitlines()[-1])
+    assert d["streams"].startswith("two") and "compact" in d["stage_ms"] and d["value"] > 0
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -385,6 +385,34 @@ def test_compress_status_word_is_clear_after_normal_calls():
         B.kv_compress_status(ws, wl.H_k, wl.L_k, wl.d, 510, B.FC_BF16, group=50)
 
 
+@pytest.mark.parametrize("wl,kind,budget", [(synth.MID_BF16, "heavy_dup", 500), (synth.MID_F32, "clustered", 333),
+                                            (synth.MID_BF16, "normal", 5000)])
+def test_select_then_compact_equals_compress(wl, kind, budget):
+    """The two halves as calls of their own: K untouched by the selection, then the same kept
+    list and the same cache bits as the one-call form and as the oracle."""
+    c = synth.compress_inputs(wl, seed=12, kind=kind)
+    L_k = wl.L_k
+    mass = torch.from_numpy(c["mass"][:, :L_k].copy()).to(DEV)
+    k, v = dev(c["k"], wl.dtype), dev(c["v"], wl.dtype)
+    kept = B.flowcache_kv_select(k, L_k, budget, mass, 7, 0.07)
+    torch.cuda.synchronize()
+    assert np.array_equal(B.to_host(k), c["k"])                       # selection only reads K
+    ws = torch.full((B.lib().flowcache_kv_compress_workspace(wl.H_k, L_k, wl.d, budget,
+                                                              B.FC_BF16 if wl.dtype == "bf16" else B.FC_F32),),
+                    0xFF, dtype=torch.uint8, device=DEV)              # a workspace the selection never saw
+    B.flowcache_kv_compact(k, v, L_k, budget, kept, workspace=ws)
+    torch.cuda.synchronize()
+    rk, rk_k, rk_v, _ = O.kv_compress(c["k"], c["v"], L_k, budget, c["mass"][:, :L_k], 7, 0.07)
+    assert np.array_equal(kept.cpu().numpy(), rk)
+    assert np.array_equal(B.to_host(k), rk_k) and np.array_equal(B.to_host(v), rk_v)
+    if budget < L_k:
+        assert B.kv_compress_status(ws, wl.H_k, L_k, wl.d, budget,
+                                    B.FC_BF16 if wl.dtype == "bf16" else B.FC_F32) == 0
+    k2, v2 = dev(c["k"], wl.dtype), dev(c["v"], wl.dtype)
+    kept2 = B.flowcache_kv_compress(k2, v2, L_k, budget, mass, 7, 0.07)
+    assert torch.equal(kept2, kept) and torch.equal(k2, k) and torch.equal(v2, v)
+
+
 def test_compress_on_strided_cache_prefix_leaves_the_rest_untouched():
     wl = synth.MID_BF16
     c = synth.compress_inputs(wl, seed=4)
