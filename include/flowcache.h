@@ -21,11 +21,12 @@
  *                             scatter half of the gather step; Sec. 3.2).
  *   flowcache_attention_mass  the importance mass alone, for explicit observation queries
  *                             (Sec. 3.3, Eq. (9); observation window of App. C.2).
- *   flowcache_kv_compress_grouped  the same at frame / chunk key granularity (App. D.2.1).
- *   flowcache_kv_select, flowcache_kv_compact  the two halves of flowcache_kv_compress.
  *   flowcache_kv_compress     joint importance-redundancy scoring, per-head top-B selection
  *                             and in-place compaction of K and V (Sec. 3.3, Eq. (10)-(12),
  *                             linear-time redundancy of App. C.2, phases of App. C.1).
+ *   flowcache_kv_select,
+ *   flowcache_kv_compact      the two halves of flowcache_kv_compress as calls of their own.
+ *   flowcache_kv_compress_grouped  the same at frame / chunk key granularity (App. D.2.1).
  *
  * Conventions common to all calls
  * -------------------------------
