@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
             asm volatile("" : "+v"(raw[i]));   // widen again here rather than keep 16 rows of doubles live
             S::widen(raw[i], x);
 #pragma unroll
-            for (int e = 0; e < EL; ++e) acc[e] += x[e] * inv;
+            for (int e = 0; e < EL; ++e) acc[e] = fma(x[e], inv, acc[e]);
         }
     }
     __shared__ double sh[kGroups][D];
