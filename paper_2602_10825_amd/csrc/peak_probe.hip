@@ -235,6 +235,36 @@ int main() {
         CK(hipEventElapsedTime(&ms, e0, e1));
     }
     printf("device read of 2 GiB: %.1f GB/s\n", (double)bytes / ms / 1e6);
+    // The same two kernels on launches of the size the streaming kernels of the path see on the
+    // SkyReels-like layer (125 MB read; 62.7 MB read + 62.7 MB written), each on a window of
+    // the 2 GiB buffers that has not been touched for 2 GiB of traffic (cold in every cache).
+    {
+        const size_t win = (size_t)125337600 / 16;   // 16-byte vectors
+        const int nwin = (int)(bytes / 16 / win);
+        float tot = 0.f;
+        const int reps = 12;
+        for (int rep = 0; rep < reps + nwin; ++rep) {
+            CK(hipEventRecord(e0));
+            read_kernel<<<2048, 256>>>(a + (size_t)(rep % nwin) * win, b, win);
+            CK(hipEventRecord(e1));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+            if (rep >= nwin) tot += ms;
+        }
+        printf("device read of 125 MB, cold: %.1f us per launch = %.1f GB/s\n", tot / reps * 1e3,
+               (double)win * 16 / (tot / reps) / 1e6);
+        tot = 0.f;
+        for (int rep = 0; rep < reps + nwin; ++rep) {
+            CK(hipEventRecord(e0));
+            copy_kernel<<<2048, 256>>>(a + (size_t)(rep % nwin) * win, b + (size_t)(rep % nwin) * win, win / 2);
+            CK(hipEventRecord(e1));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+            if (rep >= nwin) tot += ms;
+        }
+        printf("device copy of 62.7 MB, cold: %.1f us per launch = %.1f GB/s (read + write)\n",
+               tot / reps * 1e3, (double)win * 16 / (tot / reps) / 1e6);
+    }
     CK(hipDeviceSynchronize());
     return 0;
 }
