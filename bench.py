@@ -171,6 +171,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if not os.path.exists(B.LIB_PATH):      # load what is built; build only if nothing is
+        from paper_2602_10825_amd.build import build
+        build(verbose=False)
     B.lib()   # fail loudly if the HIP library is missing
     wl = {"C2": synth.C2, "C3": synth.C3, "mid": synth.MID_BF16}[args.workload]
     dev = "cuda"

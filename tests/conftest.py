@@ -28,3 +28,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _library_is_built():
+    """The tests load the library that is built in-tree; only if there is none do they build it."""
+    from paper_2602_10825_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2602_10825_amd.build import build
+        build(verbose=False)
