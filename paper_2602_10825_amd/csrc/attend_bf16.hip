@@ -42,9 +42,6 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-#ifndef FC_ATTEND_QB
-#define FC_ATTEND_QB 1
-#endif
 constexpr int BQ = 256;      // query rows per workgroup
 constexpr int BK = 64;       // keys per tile
 constexpr int NXCD = 8;
@@ -102,12 +99,10 @@ __device__ __forceinline__ void stage_tile(const u32x4_native (&kreg)[LD], const
     }
 }
 
-// QB = 32-row query blocks per wavefront: 2 -> 4 wavefronts of 64 rows (one per SIMD, 512
-// registers each), 1 -> 8 wavefronts of 32 rows (two per SIMD, 256 registers each).
-template <int D, int QB>
-__global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAttendArgs a, int tiles,
-                                                                            int per) {
-    constexpr int NT = 64 * (BQ / (32 * QB));
+constexpr int NT = 64 * (BQ / 32);   // 8 wavefronts of 32 query rows, two per SIMD
+
+template <int D>
+__global__ __launch_bounds__(NT) void attend_bf16_kernel(FcAttendArgs a, int tiles, int per) {
     constexpr int KS = D / 16;        // contraction steps of Q K^T
     constexpr int DVB = D / 32;       // 32-wide blocks of the value dimension
     constexpr int KROW = D + 8;       // padded K row (bf16): 16-byte fragment reads of 16
@@ -140,29 +135,21 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
     __shared__ __attribute__((aligned(16))) bf16_t Vs[NBUF][BK * VROW];
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[q = l32][16*step + 8*hh ..+8)
-    bf16x8_t qf[QB][KS];
-    int row_in_chunk[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        int rc = tile * BQ + wave * (32 * QB) + qb * 32 + l32;
-        row_in_chunk[qb] = rc;
-        if (rc > a.L_c - 1) rc = a.L_c - 1;
+    bf16x8_t qf[KS];
+    const int row_in_chunk = tile * BQ + wave * 32 + l32;
+    {
+        const int rc = row_in_chunk > a.L_c - 1 ? a.L_c - 1 : row_in_chunk;
         const bf16_t* qp = (const bf16_t*)a.q + (((int64_t)r * a.L_c + rc) * a.H_q + h) * D + 8 * hh;
 #pragma unroll
-        for (int st = 0; st < KS; ++st)
-            qf[qb][st] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * st);
+        for (int st = 0; st < KS; ++st) qf[st] = *reinterpret_cast<const bf16x8_t*>(qp + 16 * st);
     }
 
-    f32x16_t o[QB][DVB];
+    f32x16_t o[DVB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
+    for (int dv = 0; dv < DVB; ++dv)
 #pragma unroll
-        for (int dv = 0; dv < DVB; ++dv)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[qb][dv][i] = 0.f;
-    float m[QB], lsum[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) { m[qb] = kNegBig; lsum[qb] = 0.f; }
+        for (int i = 0; i < 16; ++i) o[dv][i] = 0.f;
+    float m = kNegBig, lsum = 0.f;
     const float c2 = a.scale * 1.4426950408889634f;
 
     const bf16_t* kbase = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
@@ -210,76 +197,72 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
     const int v_frag_off = (hh * 4 + (l16 >> 2)) * VROW + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
 
     // S^T = K Q^T of the tile in LDS buffer `BUF` (NV valid keys).
-    // sacc[qb][kb]: lane holds query l32, keys kb*32 + (i/4)*8 + hh*4 + i%4.
-    f32x16_t sacc[QB][2];
-    float mx[QB];
+    // sacc[kb]: lane holds query l32, keys kb*32 + (i/4)*8 + hh*4 + i%4.
+    f32x16_t sacc[2];
+    float mx;
 #define FC_QK(BUF, NV)                                                                        \
     {                                                                                         \
         const bf16_t* Kb_ = Ks[BUF];                                                          \
         _Pragma("unroll") for (int st = 0; st < KS; ++st) {                                   \
-            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) { /* 2*QB independent chains */  \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) { /* 2 independent chains */     \
                 const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(                       \
                     &Kb_[kb * 32 * KROW + k_frag_off + 16 * st]);                             \
-                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                           \
-                    if (st == 0) {                                                            \
-                        f32x16_t z;                                                           \
-                        _Pragma("unroll") for (int i = 0; i < 16; ++i) z[i] = 0.f;            \
-                        sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][st], z, 0, 0, 0); \
-                    } else {                                                                  \
-                        sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][st], sacc[qb][kb], 0, 0, 0); \
-                    }                                                                         \
+                if (st == 0) {                                                                \
+                    f32x16_t z;                                                               \
+                    _Pragma("unroll") for (int i = 0; i < 16; ++i) z[i] = 0.f;                \
+                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], z, 0, 0, 0); \
+                } else {                                                                      \
+                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc[kb], 0, 0, 0); \
                 }                                                                             \
             }                                                                                 \
         }                                                                                     \
         /* issue order: 8 fragment reads ahead of the matrix-core chain that uses them */     \
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);                                    \
         _Pragma("unroll") for (int g = 0; g < (2 * KS - 8) / 2; ++g) {                        \
-            __builtin_amdgcn_sched_group_barrier(0x008, 2 * QB, 0);                           \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                \
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                \
         }                                                                                     \
-        __builtin_amdgcn_sched_group_barrier(0x008, 8 * QB, 0);                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                    \
         if ((NV) < BK) { /* ragged tail of a segment: mask the keys past its end */           \
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                  \
                 _Pragma("unroll") for (int i = 0; i < 16; ++i) {                              \
                     const int key = kb * 32 + (i >> 2) * 8 + hh * 4 + (i & 3);                \
-                    if (key >= (NV)) {                                                        \
-                        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) sacc[qb][kb][i] = kNegBig; \
-                    }                                                                         \
+                    if (key >= (NV)) sacc[kb][i] = kNegBig;                                   \
                 }                                                                             \
         }                                                                                     \
     }
     // scaled row max of S (only needed when m has to be raised)
 #define FC_ROWMAX()                                                                           \
-    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                        \
-        float v = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);                                      \
+    {                                                                                         \
+        float v = fmaxf(sacc[0][0], sacc[1][0]);                                              \
         _Pragma("unroll") for (int i = 1; i < 16; ++i)                                        \
-            v = fmaxf(v, fmaxf(sacc[qb][0][i], sacc[qb][1][i]));                              \
+            v = fmaxf(v, fmaxf(sacc[0][i], sacc[1][i]));                                      \
         v = fmaxf(v, __shfl_xor(v, 32, FC_WAVE));                                             \
-        mx[qb] = v * c2;                                                                      \
+        mx = v * c2;                                                                          \
     }
     // P^T = exp2(S^T c2 - m) packed to bf16 (B operand of O^T += V^T P^T) and its row sums
 #define FC_EXP(PF, PS)                                                                        \
-    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                        \
-        const float mneg = -m[qb];                                                            \
+    {                                                                                         \
+        const float mneg = -m;                                                                \
         const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};                                   \
         float ps0 = 0.f, ps1 = 0.f;                                                           \
         _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)                                      \
             _Pragma("unroll") for (int i = 0; i < 16; i += 4) {                               \
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i], c2, mneg));     \
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 1], c2, mneg)); \
-                const float p2 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 2], c2, mneg)); \
-                const float p3 = __builtin_amdgcn_exp2f(fmaf(sacc[qb][kb][i + 3], c2, mneg)); \
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], c2, mneg));     \
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i + 1], c2, mneg)); \
+                const float p2 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i + 2], c2, mneg)); \
+                const float p3 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i + 3], c2, mneg)); \
                 const bf16x2_t lo = {(__bf16)p0, (__bf16)p1};                                 \
                 const bf16x2_t hi = {(__bf16)p2, (__bf16)p3};                                 \
                 /* the sums run over the ROUNDED weights, the ones V is multiplied with */     \
                 ps0 = __builtin_amdgcn_fdot2_f32_bf16(lo, ones, ps0, false);                  \
                 ps1 = __builtin_amdgcn_fdot2_f32_bf16(hi, ones, ps1, false);                  \
-                PF[qb][kb * 2 + (i >> 3)][i & 7] = lo[0];                                     \
-                PF[qb][kb * 2 + (i >> 3)][(i & 7) + 1] = lo[1];                               \
-                PF[qb][kb * 2 + (i >> 3)][(i & 7) + 2] = hi[0];                               \
-                PF[qb][kb * 2 + (i >> 3)][(i & 7) + 3] = hi[1];                               \
+                PF[kb * 2 + (i >> 3)][i & 7] = lo[0];                                     \
+                PF[kb * 2 + (i >> 3)][(i & 7) + 1] = lo[1];                               \
+                PF[kb * 2 + (i >> 3)][(i & 7) + 2] = hi[0];                               \
+                PF[kb * 2 + (i >> 3)][(i & 7) + 3] = hi[1];                               \
             }                                                                                 \
-        PS[qb] = ps0 + ps1;                                                                   \
+        PS = ps0 + ps1;                                                                       \
     }
     // Fetch the tile `it` points at into registers and step the iterator.
 #define FC_FETCH_NEXT()                                                                       \
@@ -310,29 +293,23 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
                 const s16x4_t hi = lds_read_tr(vp + 8 * VROW);                                \
                 const s16x8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);   \
                 const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);                         \
-                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                             \
-                    o[qb][dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, PP[qb][t], o[qb][dv], 0, 0, 0); \
+                o[dv] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, PP[t], o[dv], 0, 0, 0);   \
             }                                                                                 \
         }                                                                                     \
     }
 
     bool pending;
     int nv_pending, nv_cur = BK;
-    bf16x8_t pprev[QB][4];   // P of the previous tile, not yet multiplied into O
-    float psum[QB];
+    bf16x8_t pprev[4];   // P of the previous tile, not yet multiplied into O
+    float psum = 0.f;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) psum[qb] = 0.f;
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) pprev[qb][t][i] = (__bf16)0.f;
+        for (int i = 0; i < 8; ++i) pprev[t][i] = (__bf16)0.f;
     // buffer 2 plays "tile -1" in the first step: its V must be finite (P is zero there)
     for (int i = tid; i < BK * VROW / 8; i += NT)
         reinterpret_cast<uint4*>(Vs[2])[i] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) sacc[qb][0] = sacc[qb][1] = o[0][0];   // zeros (unused until tile 0)
+    sacc[0] = sacc[1] = o[0];   // zeros (unused until tile 0)
 
     FC_FETCH_NEXT();                                                     // tile 0 -> registers
     int b = 2, bprev = 1, bnext = 0;
@@ -346,16 +323,15 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
     for (;;) {
         if (!first) {
             FC_ROWMAX()
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                const float mnew = fmaxf(m[qb], mx[qb]);
-                const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
-                m[qb] = mnew;
-                lsum[qb] *= alpha;
+            {
+                const float mnew = fmaxf(m, mx);
+                const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+                m = mnew;
+                lsum *= alpha;
 #pragma unroll
                 for (int dv = 0; dv < DVB; ++dv)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) o[qb][dv][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) o[dv][i] *= alpha;
             }
             FC_EXP(pprev, psum)
         }
@@ -363,8 +339,7 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
         bool finished = false;
         bool raise = false;
         do {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) lsum[qb] += psum[qb];
+            lsum += psum;
             if (!pending) { finished = true; break; }
             // ---- next tile: registers -> LDS (that buffer's tile j-2 is fully consumed)
             stage_tile<LD, NT / VPR>(kreg, vreg, Ks[bnext], Vs[bnext], KROW, VROW, ld_row, ld_col);
@@ -381,30 +356,25 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
             __builtin_amdgcn_s_setprio(2);
             // ---- matrix cores: O += V P(j-1);  vector ALU: P(j) = exp2(S(j) c2 - m), row
             //      sums, bf16 pack
-            bf16x8_t pf[QB][4];
+            bf16x8_t pf[4];
             FC_PV(pprev, Vs[bprev])
             FC_EXP(pf, psum)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    // anchor: P must be computed here, next to the matrix-core work, not be
-                    // sunk to the loop latch where nothing would overlap it
-                    asm volatile("" : "+v"(pf[qb][t]));
-                    pprev[qb][t] = pf[qb][t];
-                }
+            for (int t = 0; t < 4; ++t) {
+                // anchor: P must be computed here, next to the matrix-core work, not be
+                // sunk to the loop latch where nothing would overlap it
+                asm volatile("" : "+v"(pf[t]));
+                pprev[t] = pf[t];
+            }
             // issue order: V fragments are read 4 fragments (8 loads) ahead of their use
             __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
             for (int f = 0; f < 4 * DVB; ++f) {
-                __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 if (f + 4 < 4 * DVB) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             }
             __builtin_amdgcn_s_setprio(0);
-            bool too_big = false;
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) too_big = too_big || (psum[qb] > kTooBig);
-            raise = __any(too_big);
+            raise = __any(psum > kTooBig);
         } while (!raise);
         if (finished) break;
     }
@@ -416,12 +386,11 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
 #undef FC_FETCH_NEXT
 
     // ---- epilogue: normalise, store O (bf16) and the row log-sum-exp
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const float ltot = lsum[qb] + __shfl_xor(lsum[qb], 32, FC_WAVE);
+    {
+        const float ltot = lsum + __shfl_xor(lsum, 32, FC_WAVE);
         const float inv = 1.0f / ltot;
-        if (row_in_chunk[qb] < a.L_c) {
-            const int64_t row = (int64_t)r * a.L_c + row_in_chunk[qb];
+        if (row_in_chunk < a.L_c) {
+            const int64_t row = (int64_t)r * a.L_c + row_in_chunk;
             bf16_t* op = (bf16_t*)a.out + (row * a.H_q + h) * D;
 #pragma unroll
             for (int dv = 0; dv < DVB; ++dv)
@@ -429,15 +398,15 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
                 for (int g = 0; g < 4; ++g) {
                     const int e0 = dv * 32 + g * 8 + hh * 4;
                     uint2 pk;
-                    pk.x = (uint32_t)f32_to_bf16(o[qb][dv][4 * g] * inv) |
-                           ((uint32_t)f32_to_bf16(o[qb][dv][4 * g + 1] * inv) << 16);
-                    pk.y = (uint32_t)f32_to_bf16(o[qb][dv][4 * g + 2] * inv) |
-                           ((uint32_t)f32_to_bf16(o[qb][dv][4 * g + 3] * inv) << 16);
+                    pk.x = (uint32_t)f32_to_bf16(o[dv][4 * g] * inv) |
+                           ((uint32_t)f32_to_bf16(o[dv][4 * g + 1] * inv) << 16);
+                    pk.y = (uint32_t)f32_to_bf16(o[dv][4 * g + 2] * inv) |
+                           ((uint32_t)f32_to_bf16(o[dv][4 * g + 3] * inv) << 16);
                     *reinterpret_cast<uint2*>(op + e0) = pk;
                 }
             if (a.lse && hh == 0)
                 a.lse[(int64_t)h * a.A * a.L_c + row] =
-                    (m[qb] + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
+                    (m + __builtin_amdgcn_logf(ltot)) * 0.6931471805599453f;
         }
     }
 }
@@ -445,16 +414,14 @@ __global__ __launch_bounds__(64 * (BQ / (32 * QB))) void attend_bf16_kernel(FcAt
 }  // namespace
 
 int fc_launch_attend_bf16(const FcAttendArgs& a, hipStream_t s) {
-    constexpr int QB = FC_ATTEND_QB;
-    constexpr int NT = 64 * (BQ / (32 * QB));
     const int tiles = (a.L_c + BQ - 1) / BQ;
     const int items = a.H_q * tiles;
     const int per = (items + NXCD - 1) / NXCD;
     const dim3 grid((unsigned)(NXCD * per * a.A));
     if (a.d == 128)
-        attend_bf16_kernel<128, QB><<<grid, NT, 0, s>>>(a, tiles, per);
+        attend_bf16_kernel<128><<<grid, NT, 0, s>>>(a, tiles, per);
     else if (a.d == 64)
-        attend_bf16_kernel<64, QB><<<grid, NT, 0, s>>>(a, tiles, per);
+        attend_bf16_kernel<64><<<grid, NT, 0, s>>>(a, tiles, per);
     else
         return FC_UNSUPPORTED;
     FC_LAUNCH_CHECK();
