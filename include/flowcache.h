@@ -40,7 +40,8 @@
  *    must be stream-ordered.
  *  - Return value: FC_OK or an error code.  Argument errors are detected and returned
  *    BEFORE any HIP call is made, so they can be exercised on a machine without a GPU.
- *    No exception crosses the boundary; the library keeps no global state.
+ *    No exception crosses the boundary; the library keeps no state between calls (except the
+ *    device address of its own scratch buffer, see flowcache_chunk_decide_noalloc).
  *  - dtype FC_F32: float tensors, fp32 arithmetic.  FC_BF16: bfloat16 tensors, bf16 x bf16
  *    -> fp32 matrix-core products, fp32 softmax state, bf16 output.
  *  - The recompute list (recompute_idx, n_recompute) lives on the device, so the host
@@ -111,6 +112,28 @@ int flowcache_chunk_decide(const void* x_cur, const void* x_prev, fc_dtype dtype
                            int32_t* recompute_idx, int32_t* n_recompute, void* x_compact,
                            void* workspace, size_t workspace_bytes, fc_stream stream);
 size_t flowcache_chunk_decide_workspace(int A, int64_t chunk_elems);
+
+/*
+ * flowcache_chunk_decide for callers that cannot allocate device memory and have no workspace
+ * to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (minus the workspace), same kernels and bit-identical results.
+ * The block partials go to a buffer of FC_DECIDE_SCRATCH_BYTES that the library itself holds
+ * in device memory (one per GPU, for the life of the process).  The call allocates and frees
+ * nothing, enqueues on `stream` and returns without synchronising.
+ *   - Every call on a GPU shares that GPU's buffer: calls that may overlap on one GPU (two
+ *     streams, two threads) race and must be ordered by the caller.  Nothing in the buffer has
+ *     to survive between calls and nothing in it has to start at zero.
+ *   - A launch whose partials would not fit (flowcache_chunk_decide_workspace(A, chunk_elems) >
+ *     FC_DECIDE_SCRATCH_BYTES) is rejected with FC_WORKSPACE_TOO_SMALL before any HIP call;
+ *     with A <= FC_MAX_ACTIVE the launches of this version never need more than 32 KiB.
+ *   - FC_HIP_ERROR if the buffer's address cannot be obtained on the current device.
+ */
+#define FC_DECIDE_SCRATCH_BYTES 32768
+int flowcache_chunk_decide_noalloc(const void* x_cur, const void* x_prev, fc_dtype dtype, int A,
+                                   int64_t chunk_elems, const int32_t* step_idx, int warmup_m,
+                                   double eps, double* acc, double* l1rel,
+                                   uint8_t* recompute_mask, int32_t* recompute_idx,
+                                   int32_t* n_recompute, void* x_compact, fc_stream stream);
 
 /*
  * Uniform reuse policy (Fig. 2, top: the policy the chunkwise one is compared with): the relative L1

@@ -24,7 +24,7 @@ FC_MAX_ACTIVE = 16
 
 EXPORTS = (
     "flowcache_status_string", "flowcache_version",
-    "flowcache_chunk_decide", "flowcache_chunk_decide_workspace",
+    "flowcache_chunk_decide", "flowcache_chunk_decide_workspace", "flowcache_chunk_decide_noalloc",
     "flowcache_uniform_decide", "flowcache_residual_apply",
     "flowcache_attend", "flowcache_attend_workspace", "flowcache_scatter_kv",
     "flowcache_attention_mass", "flowcache_attention_mass_workspace",
@@ -66,6 +66,9 @@ def lib() -> ctypes.CDLL:
     L.flowcache_chunk_decide.restype = c_int
     L.flowcache_chunk_decide.argtypes = [c_vp, c_vp, c_int, c_int, c_i64, c_vp, c_int, c_d, c_vp,
                                          c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    L.flowcache_chunk_decide_noalloc.restype = c_int
+    L.flowcache_chunk_decide_noalloc.argtypes = [c_vp, c_vp, c_int, c_int, c_i64, c_vp, c_int, c_d, c_vp,
+                                                 c_vp, c_vp, c_vp, c_vp, c_vp, c_vp]
     L.flowcache_uniform_decide.restype = c_int
     L.flowcache_uniform_decide.argtypes = L.flowcache_chunk_decide.argtypes
     L.flowcache_residual_apply.restype = c_int
@@ -174,6 +177,21 @@ def flowcache_chunk_decide(x_cur: torch.Tensor, x_prev: torch.Tensor, step_idx: 
     _check("flowcache_chunk_decide", st)
     return {"recompute_mask": mask, "recompute_idx": idx, "n_recompute": n_rec, "l1rel": l1rel,
             "acc": acc, "x_compact": x_compact}
+
+
+def flowcache_chunk_decide_noalloc(x_cur: torch.Tensor, x_prev: torch.Tensor, step_idx: torch.Tensor,
+                                   warmup_m: int, eps: float, acc: torch.Tensor, l1rel: torch.Tensor,
+                                   recompute_mask: torch.Tensor, recompute_idx: torch.Tensor,
+                                   n_recompute: torch.Tensor, x_compact: Optional[torch.Tensor] = None,
+                                   stream=None) -> None:
+    """flowcache_chunk_decide without a workspace: the caller passes every input and output, the
+    library uses its own fixed scratch buffer, and nothing is allocated on either side."""
+    A = x_cur.shape[0]
+    st = lib().flowcache_chunk_decide_noalloc(
+        _ptr(x_cur), _ptr(x_prev), _dtype_code(x_cur), A, x_cur[0].numel(), _ptr(step_idx),
+        int(warmup_m), float(eps), _ptr(acc), _ptr(l1rel), _ptr(recompute_mask), _ptr(recompute_idx),
+        _ptr(n_recompute), _ptr(x_compact), _stream(stream))
+    _check("flowcache_chunk_decide_noalloc", st)
 
 
 def flowcache_uniform_decide(x_cur: torch.Tensor, x_prev: torch.Tensor, step_idx: torch.Tensor,

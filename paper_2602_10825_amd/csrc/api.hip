@@ -70,6 +70,27 @@ int flowcache_chunk_decide(const void* x_cur, const void* x_prev, fc_dtype dtype
     return fc_launch_decide(a, (hipStream_t)stream);
 }
 
+int flowcache_chunk_decide_noalloc(const void* x_cur, const void* x_prev, fc_dtype dtype, int A,
+                                   int64_t chunk_elems, const int32_t* step_idx, int warmup_m,
+                                   double eps, double* acc, double* l1rel,
+                                   uint8_t* recompute_mask, int32_t* recompute_idx,
+                                   int32_t* n_recompute, void* x_compact, fc_stream stream) {
+    if (!x_cur || !x_prev || !step_idx || !acc || !recompute_mask || !recompute_idx || !n_recompute)
+        return FC_INVALID_ARGUMENT;
+    if (bad_dtype(dtype) || A < 1 || A > FC_MAX_ACTIVE || chunk_elems < 1 || warmup_m < 0)
+        return FC_INVALID_ARGUMENT;
+    if (!(eps >= 0.0) || !std::isfinite(eps)) return FC_INVALID_ARGUMENT;
+    // the block partials of this launch must fit the library's own scratch
+    if (flowcache_chunk_decide_workspace(A, chunk_elems) > (size_t)FC_DECIDE_SCRATCH_BYTES)
+        return FC_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    const int st = fc_decide_scratch(&ws);
+    if (st != FC_OK) return st;
+    FcDecideArgs a{x_cur, x_prev, dtype, A, chunk_elems, step_idx, warmup_m, eps, acc, l1rel,
+                   recompute_mask, recompute_idx, n_recompute, x_compact, ws, 0};
+    return fc_launch_decide(a, (hipStream_t)stream);
+}
+
 int flowcache_uniform_decide(const void* x_cur, const void* x_prev, fc_dtype dtype, int A,
                              int64_t chunk_elems, const int32_t* step_idx, int warmup_m,
                              double eps, double* acc_global, double* l1rel,

@@ -9,6 +9,8 @@
 //                      ascending recompute list and count.
 //   3. gather_chunks   block copies x_cur[idx[r]] -> x_compact[r] for r < n_recompute
 //                      (the count is read on the device: no host round trip).
+#include <atomic>
+
 #include "fc_common.hpp"
 
 namespace {
@@ -257,4 +259,30 @@ int fc_decide_blocks_per_chunk(int A, int64_t chunk_elems, fc_dtype dtype) {
 
 int fc_launch_decide(const FcDecideArgs& a, hipStream_t s) {
     return a.dtype == FC_BF16 ? launch_typed<bf16_t>(a, s) : launch_typed<float>(a, s);
+}
+
+// ---- library-owned scratch for the entry point that allocates nothing ---------------------
+// The block partials of decide_reduce, for callers that cannot bring a workspace.  Every GPU
+// the library runs on holds its own copy of the array for the life of the process.  In host
+// code the array's name is only a stand-in for the symbol: the device address comes from
+// hipGetSymbolAddress, is looked up once per device (with that device current) and is what
+// the kernels receive.
+static __device__ __align__(256) unsigned char scratch[FC_DECIDE_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+}  // namespace
+
+int fc_decide_scratch(void** ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FC_HIP_ERROR;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // racing first calls on one device look the same address up twice: harmless
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FC_HIP_ERROR;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return FC_OK;
 }

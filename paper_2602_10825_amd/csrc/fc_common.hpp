@@ -95,6 +95,8 @@ struct FcDecideArgs {
 };
 int fc_decide_blocks_per_chunk(int A, int64_t chunk_elems, fc_dtype dtype);
 int fc_launch_decide(const FcDecideArgs& a, hipStream_t s);
+// device address, on the current device, of the library's own FC_DECIDE_SCRATCH_BYTES of scratch
+int fc_decide_scratch(void** ptr);
 
 struct FcResidualArgs {
     const void* x_cur; const void* y_compact; void* residual; void* out; fc_dtype dtype;
