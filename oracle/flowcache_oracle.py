@@ -23,7 +23,7 @@ special cases) live in ``tests/test_oracle_*.py``.  Pin status:
   compact_kv, kv_compress .................. pinned (identity case, exact copies)
   kv_compress_grouped ...................... pinned (group = 1 is kv_compress; identical tokens
                                              inside each group reduce it to kv_compress on one
-                                             token per group; hand-worked case)
+                                             token per group; hand-worked case; means stay float64)
   Parity unpinned (the paper gives no value): the max-pool kernel size, the exact
   attention mask and the order of the surviving tokens rest on the readings below.
 
@@ -424,9 +424,9 @@ def kv_compress_grouped(k_cache: np.ndarray, v_cache: np.ndarray, L_k: int, budg
 
     The paper names the granularities (token, frame, chunk) without saying how a group of keys
     is represented.  Reading: the group's key is the mean of its keys, its importance the mean
-    of its tokens' mass, each a float64 mean rounded once to float32; Eq. (10)-(12) and the
-    top-B selection then run over groups exactly as they do over tokens, and all tokens of a
-    kept group are kept.  Returns (kept token indices [H, budget], new K, new V, group scores).
+    of its tokens' mass, both plain float64 means (no intermediate rounding); Eq. (10)-(12) and
+    the top-B selection then run over groups exactly as they do over tokens, and all tokens of
+    a kept group are kept.  Returns (kept token indices [H, budget], new K, new V, group scores).
     """
     assert L_k % group == 0 and budget % group == 0
     H = k_cache.shape[0]
@@ -439,9 +439,8 @@ def kv_compress_grouped(k_cache: np.ndarray, v_cache: np.ndarray, L_k: int, budg
     scores = []
     for h in range(H):
         kw = widen(k_cache[h, :L_k]).reshape(G, group, -1)
-        kg = (kw.sum(axis=1) / group).astype(np.float32)
-        mg = (np.asarray(mass[h, :L_k], dtype=np.float64).reshape(G, group).sum(axis=1) / group
-              ).astype(np.float32)
+        kg = kw.sum(axis=1) / group
+        mg = np.asarray(mass[h, :L_k], dtype=np.float64).reshape(G, group).sum(axis=1) / group
         sc = selection_scores(kg, mg, pool_k, lam)
         groups = select_top_b(sc, Bg)
         kept[h] = (np.asarray(groups, dtype=np.int64)[:, None] * group

@@ -229,3 +229,15 @@ def test_grouped_compress_hand_worked():
     # identity when the budget covers everything
     kept, k_new, _, _ = O.kv_compress_grouped(k, v, 6, 6, 2, mass, 1, 1.0)
     assert kept.tolist() == [list(range(6))] and np.array_equal(k_new, k)
+
+
+def test_grouped_means_are_not_rounded_to_float32():
+    # two groups whose mean mass differs by 2^-25: one float32 rounding of the means would make
+    # them tie (and the lower group win); as float64 means the second group is strictly ahead
+    k = np.array([[[1, 0], [1, 0], [0, 1], [0, 1], [1, 1], [1, 1]]], np.float32)
+    v = np.zeros((1, 6, 2), np.float32)
+    step = np.float32(2.0 ** -24)
+    mass = np.array([[0.5, 0.5, 0.5, np.float32(0.5) + step, 0.1, 0.1]], np.float32)
+    assert np.float32((0.5 + (0.5 + 2.0 ** -24)) / 2) == np.float32(0.5)       # the tie a rounding would create
+    kept, _, _, sc = O.kv_compress_grouped(k, v, 6, 2, 2, mass, 1, 1.0)
+    assert sc[0][1] > sc[0][0] and kept.tolist() == [[2, 3]]
