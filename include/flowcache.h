@@ -311,8 +311,8 @@ int flowcache_kv_compact(void* k_cache, void* v_cache, int64_t kv_head_stride,
  * The same compression with keys scored and kept at a coarser granularity (the frame- and
  * chunk-level key granularities of the ablation in App. D.2.1).  The first L_k positions
  * are split into groups of `group` consecutive tokens (a latent frame, or a chunk).  A group
- * is represented by the mean of its keys and the mean of its tokens' mass (float64 sums,
- * rounded once to float32); Eq. (10)-(12) and the top-B selection run over the groups exactly
+ * is represented by the mean of its keys and the mean of its tokens' mass (float64 sums and
+ * means, kept as float64); Eq. (10)-(12) and the top-B selection run over the groups exactly
  * as they run over tokens in flowcache_kv_compress; every token of a kept group is kept.
  *
  *   group    tokens per group, >= 1 (1 = flowcache_kv_compress); L_k and budget (both in

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libflowcache.so")
 FC_F32, FC_BF16 = 0, 1
 FC_OK = 0
 FC_INVALID_ARGUMENT = 1
+FC_HIP_ERROR = 4
 FC_MAX_ACTIVE = 16
 
 EXPORTS = (
@@ -315,9 +316,12 @@ def flowcache_attention_mass(q_obs: torch.Tensor, k_cache: torch.Tensor, mass_le
 def flowcache_kv_compress(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int, budget: int,
                           mass: torch.Tensor, pool_k: int = 7, lam: float = 0.07,
                           kept_idx: Optional[torch.Tensor] = None,
-                          workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                          workspace: Optional[torch.Tensor] = None, stream=None,
+                          check_status: bool = False) -> torch.Tensor:
     """Compress positions [0, L_k) of the caches to ``budget`` per head, in place.  Returns
-    kept_idx ``[H_k, min(budget, L_k)]`` int32 (ascending original positions)."""
+    kept_idx ``[H_k, min(budget, L_k)]`` int32 (ascending original positions).  With
+    ``check_status`` the call synchronises and raises if a bounded wait of the in-place
+    compaction ran out (the caches are then unspecified)."""
     H_k, capacity, d = k_cache.shape
     dev = k_cache.device
     assert k_cache.stride(2) == 1 and v_cache.stride() == k_cache.stride()
@@ -334,6 +338,8 @@ def flowcache_kv_compress(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int
                                  float(lam), _ptr(kept_idx), _ptr(workspace), workspace.numel(),
                                  _stream(stream))
     _check("flowcache_kv_compress", st)
+    if check_status:
+        _raise_on_compaction_status("flowcache_kv_compress", workspace, H_k, L_k, d, budget, code, 1)
     return kept_idx
 
 
@@ -361,7 +367,7 @@ def flowcache_kv_select(k_cache: torch.Tensor, L_k: int, budget: int, mass: torc
 
 def flowcache_kv_compact(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int, budget: int,
                          kept_idx: torch.Tensor, workspace: Optional[torch.Tensor] = None,
-                         stream=None) -> None:
+                         stream=None, check_status: bool = False) -> None:
     """Moves row ``kept_idx[h][i]`` of K and V to position i, in place."""
     H_k, capacity, d = k_cache.shape
     dev = k_cache.device
@@ -376,12 +382,15 @@ def flowcache_kv_compact(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int,
                                 code, H_k, d, int(L_k), int(budget), _ptr(kept_idx), _ptr(workspace),
                                 workspace.numel(), _stream(stream))
     _check("flowcache_kv_compact", st)
+    if check_status:
+        _raise_on_compaction_status("flowcache_kv_compact", workspace, H_k, L_k, d, budget, code, 1)
 
 
 def flowcache_kv_compress_grouped(k_cache: torch.Tensor, v_cache: torch.Tensor, L_k: int, budget: int,
                                   group: int, mass: torch.Tensor, pool_k: int = 7, lam: float = 0.07,
                                   kept_idx: Optional[torch.Tensor] = None,
-                                  workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                                  workspace: Optional[torch.Tensor] = None, stream=None,
+                                  check_status: bool = False) -> torch.Tensor:
     """As flowcache_kv_compress, with keys scored and kept in groups of ``group`` consecutive
     tokens (``L_k`` and ``budget`` are token counts, multiples of ``group``)."""
     H_k, capacity, d = k_cache.shape
@@ -400,6 +409,8 @@ def flowcache_kv_compress_grouped(k_cache: torch.Tensor, v_cache: torch.Tensor, 
                                          int(pool_k), float(lam), _ptr(kept_idx), _ptr(workspace),
                                          workspace.numel(), _stream(stream))
     _check("flowcache_kv_compress_grouped", st)
+    if check_status:
+        _raise_on_compaction_status("flowcache_kv_compress_grouped", workspace, H_k, L_k, d, budget, code, group)
     return kept_idx
 
 
@@ -411,6 +422,13 @@ def kv_compress_status(workspace: torch.Tensor, H_k: int, L_k: int, d: int, budg
     if off == ctypes.c_size_t(-1).value:
         raise FlowCacheError("flowcache_kv_compress_status_offset", FC_INVALID_ARGUMENT)
     return int(workspace[off:off + 4].view(torch.int32).item())
+
+
+def _raise_on_compaction_status(call: str, workspace: torch.Tensor, H_k: int, L_k: int, d: int,
+                                budget: int, dtype_code: int, group: int) -> None:
+    if budget < L_k and kv_compress_status(workspace, H_k, L_k, d, budget, dtype_code, group) != 0:
+        raise FlowCacheError(call + ": a wait of the in-place compaction ran out, caches unspecified",
+                             FC_HIP_ERROR)
 
 
 # ---- host-side tick scheduler (flowcache_sched.h) ------------------------------------------

@@ -50,7 +50,10 @@ struct Slice {
         return *reinterpret_cast<const raw_t*>(row + u * EL);
     }
     static __device__ __forceinline__ void widen(const raw_t& r, double (&x)[EL]) {
-        if constexpr (sizeof(T) == 2) {
+        if constexpr (sizeof(T) == 8) {
+#pragma unroll
+            for (int e = 0; e < EL; ++e) x[e] = __hiloint2double((int)r[2 * e + 1], (int)r[2 * e]);
+        } else if constexpr (sizeof(T) == 2) {
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
                 x[2 * w] = (double)bf16lo_to_f32(r[w]);
@@ -269,14 +272,15 @@ __device__ __forceinline__ uint64_t score_key(double score) {
 
 
 // ---- keys: Eq. (10)-(12) per token, fully parallel ------------------------------------
+template <typename MT>   // importance as given (float) or pooled over a key group (double)
 __global__ __launch_bounds__(kThreads) void score_keys_kernel(
-    const double* __restrict__ e_all, const float* __restrict__ mass_all,
+    const double* __restrict__ e_all, const MT* __restrict__ mass_all,
     const double* __restrict__ pz_all, int nblkz, int L, int pool_k, double lambda,
     uint64_t* __restrict__ keys_all, uint64_t* __restrict__ pminmax, uint32_t* __restrict__ hist_all,
     uint32_t* __restrict__ sync, int ntile) {
     const int h = blockIdx.y, tid = threadIdx.x;
     const double* e = e_all + (int64_t)h * L;
-    const float* mass = mass_all + (int64_t)h * L;
+    const MT* mass = mass_all + (int64_t)h * L;
     uint64_t* keys = keys_all + (int64_t)h * L;
     __shared__ double shd[kThreads];
     __shared__ uint64_t shu[kThreads / FC_WAVE];
@@ -294,21 +298,22 @@ __global__ __launch_bounds__(kThreads) void score_keys_kernel(
     const int half = pool_k / 2;
     const int j0 = blockIdx.x * kTokBlk;
     double ev[kItems];
-    float imp[kItems];
+    MT imp[kItems];
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         const int j = j0 + i * kThreads + tid;
         ev[i] = (j < L) ? e[j] : 0.0;
-        imp[i] = (j < L) ? mass[j] : 0.f;
+        imp[i] = (j < L) ? mass[j] : (MT)0;
     }
     for (int d = 1; d <= half; ++d) {   // Eq. (10): window max, -inf outside [0, L)
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
             const int j = j0 + i * kThreads + tid;
             if (j < L) {
-                const float lo = (j - d >= 0) ? mass[j - d] : imp[i];
-                const float hi = (j + d < L) ? mass[j + d] : imp[i];
-                imp[i] = fmaxf(imp[i], fmaxf(lo, hi));
+                const MT lo = (j - d >= 0) ? mass[j - d] : imp[i];
+                const MT hi = (j + d < L) ? mass[j + d] : imp[i];
+                const MT nb = lo > hi ? lo : hi;
+                imp[i] = imp[i] > nb ? imp[i] : nb;
             }
         }
     }
@@ -730,19 +735,21 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     return w;
 }
 
-template <typename T, int D>
-int launch_typed(const FcCompressArgs& a, hipStream_t s, bool compact = true) {
+template <typename T, int D, typename MT>
+int launch_typed(const FcCompressArgs& a, const MT* mass, hipStream_t s, bool compact = true) {
     const WsLayout w = layout(a.H_k, a.L_k, a.d, a.budget, a.dtype);
-    if (a.phase == 2) {   // rows only: the kept list is the caller's
-        uint32_t* sync2 = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(a.ws) + w.sync);
-        reset_sync_kernel<<<a.H_k, kThreads, 0, s>>>(sync2, a.H_k, w.ntile);
-        FC_LAUNCH_CHECK();
-        constexpr int VPR2 = D * (int)sizeof(T) / 16;
-        const int64_t hs2 = a.head_stride * (int64_t)sizeof(T) / 16, ts2 = a.tok_stride * (int64_t)sizeof(T) / 16;
-        compact_rows_kernel<VPR2><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
-            (uint4*)a.k_cache, (uint4*)a.v_cache, hs2, ts2, a.H_k, a.L_k, a.budget, w.ntile, a.kept, sync2);
-        FC_LAUNCH_CHECK();
-        return FC_OK;
+    if constexpr (sizeof(T) <= 4) {   // (the float64 instantiation scores pooled keys: no rows to move)
+        if (a.phase == 2) {           // rows only: the kept list is the caller's
+            uint32_t* sync2 = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(a.ws) + w.sync);
+            reset_sync_kernel<<<a.H_k, kThreads, 0, s>>>(sync2, a.H_k, w.ntile);
+            FC_LAUNCH_CHECK();
+            constexpr int VPR2 = D * (int)sizeof(T) / 16;
+            const int64_t hs2 = a.head_stride * (int64_t)sizeof(T) / 16, ts2 = a.tok_stride * (int64_t)sizeof(T) / 16;
+            compact_rows_kernel<VPR2><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
+                (uint4*)a.k_cache, (uint4*)a.v_cache, hs2, ts2, a.H_k, a.L_k, a.budget, w.ntile, a.kept, sync2);
+            FC_LAUNCH_CHECK();
+            return FC_OK;
+        }
     }
     char* ws = reinterpret_cast<char*>(a.ws);
     double2* tokinfo = reinterpret_cast<double2*>(ws + w.tokinfo);
@@ -765,7 +772,7 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s, bool compact = true) {
     mean_sim_kernel<T, D><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
                                                                   a.L_k, tokinfo, ssum, e, pz);
     FC_LAUNCH_CHECK();
-    score_keys_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(e, a.mass, pz, w.nblk, a.L_k, a.pool_k,
+    score_keys_kernel<MT><<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(e, mass, pz, w.nblk, a.L_k, a.pool_k,
                                                               a.lambda, keys, pminmax, hist, sync, w.ntile);
     FC_LAUNCH_CHECK();
     key_hist_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, pminmax, a.L_k, hist);
@@ -775,22 +782,24 @@ int launch_typed(const FcCompressArgs& a, hipStream_t s, bool compact = true) {
     write_kept_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, sel, a.L_k, a.budget, a.kept);
     FC_LAUNCH_CHECK();
     if (!compact || a.phase == 1) return FC_OK;   // scoring and selection only
-    constexpr int VPR = D * (int)sizeof(T) / 16;
-    const int64_t hs = a.head_stride * (int64_t)sizeof(T) / 16, ts = a.tok_stride * (int64_t)sizeof(T) / 16;
-    compact_rows_kernel<VPR><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
-        (uint4*)a.k_cache, (uint4*)a.v_cache, hs, ts, a.H_k, a.L_k, a.budget, w.ntile, a.kept, sync);
-    FC_LAUNCH_CHECK();
+    if constexpr (sizeof(T) <= 4) {
+        constexpr int VPR = D * (int)sizeof(T) / 16;
+        const int64_t hs = a.head_stride * (int64_t)sizeof(T) / 16, ts = a.tok_stride * (int64_t)sizeof(T) / 16;
+        compact_rows_kernel<VPR><<<dim3(w.ntile, a.H_k), kThreads, 0, s>>>(
+            (uint4*)a.k_cache, (uint4*)a.v_cache, hs, ts, a.H_k, a.L_k, a.budget, w.ntile, a.kept, sync);
+        FC_LAUNCH_CHECK();
+    }
     return FC_OK;
 }
 
 // ---- key granularity above the token (frame- or chunk-level keys, App. D.2.1) ------------
 // Group g = tokens [g*group, (g+1)*group): its key is the mean key, its importance the mean
-// mass, both summed in float64 in a fixed order and rounded once to float32.
+// mass, both float64 sums in a fixed order divided by the group size and kept as float64.
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void group_pool_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int group, int G,
-    const float* __restrict__ mass, int L, float* __restrict__ k_pooled,
-    float* __restrict__ mass_pooled) {
+    const float* __restrict__ mass, int L, double* __restrict__ k_pooled,
+    double* __restrict__ mass_pooled) {
     typedef Slice<T, D> S;
     constexpr int EL = S::EL;
     const int g = blockIdx.x, h = blockIdx.y;
@@ -816,9 +825,9 @@ __global__ __launch_bounds__(kThreads) void group_pool_kernel(
         double t = 0.0;
 #pragma unroll
         for (int k = 0; k < kGroups; ++k) t += sh[k][threadIdx.x];
-        k_pooled[((int64_t)h * G + g) * D + threadIdx.x] = (float)(t / (double)group);
+        k_pooled[((int64_t)h * G + g) * D + threadIdx.x] = t / (double)group;
     }
-    if (threadIdx.x == 0) mass_pooled[(int64_t)h * G + g] = (float)(m / (double)group);
+    if (threadIdx.x == 0) mass_pooled[(int64_t)h * G + g] = m / (double)group;
 }
 
 // kept groups -> kept token positions; also resets the ticket / flag words the token-level
@@ -848,8 +857,8 @@ GroupedLayout grouped_layout(int H, int L, int d, int budget, int group) {
     w.Bg = budget / group;
     w.ntile = (budget + kTileRows - 1) / kTileRows;
     size_t off = 0;
-    w.k_pooled = off;    off += fc_align_up((size_t)H * w.G * d * 4);
-    w.mass_pooled = off; off += fc_align_up((size_t)H * w.G * 4);
+    w.k_pooled = off;    off += fc_align_up((size_t)H * w.G * d * 8);
+    w.mass_pooled = off; off += fc_align_up((size_t)H * w.G * 8);
     w.kept_groups = off; off += fc_align_up((size_t)H * (w.Bg > 0 ? w.Bg : 1) * 4);
     w.inner = off;       off += layout(H, w.G, d, w.Bg > 0 ? w.Bg : 1, FC_F32).total;
     w.sync = off;        off += fc_align_up(((size_t)H * w.ntile + 64 * ((size_t)H + 1)) * 4);
@@ -861,8 +870,8 @@ template <typename T, int D>
 int launch_grouped(const FcCompressArgs& a, hipStream_t s) {
     const GroupedLayout w = grouped_layout(a.H_k, a.L_k, a.d, a.budget, a.group);
     char* ws = reinterpret_cast<char*>(a.ws);
-    float* k_pooled = reinterpret_cast<float*>(ws + w.k_pooled);
-    float* mass_pooled = reinterpret_cast<float*>(ws + w.mass_pooled);
+    double* k_pooled = reinterpret_cast<double*>(ws + w.k_pooled);
+    double* mass_pooled = reinterpret_cast<double*>(ws + w.mass_pooled);
     int32_t* kept_groups = reinterpret_cast<int32_t*>(ws + w.kept_groups);
     uint32_t* sync = reinterpret_cast<uint32_t*>(ws + w.sync);
     group_pool_kernel<T, D><<<dim3(w.G, a.H_k), kThreads, 0, s>>>(
@@ -873,9 +882,9 @@ int launch_grouped(const FcCompressArgs& a, hipStream_t s) {
     FcCompressArgs b = a;
     b.k_cache = k_pooled; b.v_cache = k_pooled;
     b.head_stride = (int64_t)w.G * D; b.tok_stride = D; b.dtype = FC_F32;
-    b.L_k = w.G; b.budget = w.Bg; b.mass = mass_pooled; b.kept = kept_groups; b.ws = ws + w.inner;
+    b.L_k = w.G; b.budget = w.Bg; b.mass = nullptr; b.kept = kept_groups; b.ws = ws + w.inner;
     b.group = 1;
-    const int st = launch_typed<float, D>(b, s, false);
+    const int st = launch_typed<double, D, double>(b, mass_pooled, s, false);
     if (st != FC_OK) return st;
     int gx = (int)(((int64_t)w.Bg * a.group + kThreads * 4 - 1) / (kThreads * 4));
     gx = gx < 1 ? 1 : (gx > 256 ? 256 : gx);
@@ -924,11 +933,11 @@ int fc_launch_compress(const FcCompressArgs& a, hipStream_t s) {
         return FC_UNSUPPORTED;
     }
     if (a.dtype == FC_BF16) {
-        if (a.d == 128) return launch_typed<bf16_t, 128>(a, s);
-        if (a.d == 64) return launch_typed<bf16_t, 64>(a, s);
+        if (a.d == 128) return launch_typed<bf16_t, 128, float>(a, a.mass, s);
+        if (a.d == 64) return launch_typed<bf16_t, 64, float>(a, a.mass, s);
     } else {
-        if (a.d == 128) return launch_typed<float, 128>(a, s);
-        if (a.d == 64) return launch_typed<float, 64>(a, s);
+        if (a.d == 128) return launch_typed<float, 128, float>(a, a.mass, s);
+        if (a.d == 64) return launch_typed<float, 64, float>(a, a.mass, s);
     }
     return FC_UNSUPPORTED;
 }

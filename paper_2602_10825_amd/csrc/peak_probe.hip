@@ -140,6 +140,64 @@ __global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ s, 
     if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u) d[0] = acc;   // keeps the loads alive
 }
 
+// U 16-byte vectors in flight per thread: all loads of a round are issued before its stores
+template <int U>
+__global__ __launch_bounds__(256) void copy_unrolled(const uint4* __restrict__ s, uint4* __restrict__ d, size_t n) {
+    const size_t stride = (size_t)gridDim.x * 256 * U;
+    for (size_t i0 = (size_t)blockIdx.x * 256 * U + threadIdx.x; i0 < n; i0 += stride) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i0 + (size_t)u * 256 < n) v[u] = s[i0 + (size_t)u * 256];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i0 + (size_t)u * 256 < n) d[i0 + (size_t)u * 256] = v[u];
+    }
+}
+
+template <int U>
+__global__ __launch_bounds__(256) void read_unrolled(const uint4* __restrict__ s, uint4* __restrict__ d, size_t n) {
+    const size_t stride = (size_t)gridDim.x * 256 * U;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t i0 = (size_t)blockIdx.x * 256 * U + threadIdx.x; i0 < n; i0 += stride) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            v[u] = (i0 + (size_t)u * 256 < n) ? s[i0 + (size_t)u * 256] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+    }
+    if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u) d[0] = acc;   // keeps the loads alive
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(uint4* __restrict__ d, size_t n) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    const uint4 v = make_uint4(1, 2, 3, 4);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) d[i] = v;
+}
+
+template <bool RANDOM>
+__global__ __launch_bounds__(256) void mfma16_loop(const bf16x8* in, float* out, int iters) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    bf16x8 a[4], b[4];
+    for (int j = 0; j < 4; ++j) {
+        if (RANDOM) {
+            a[j] = in[(threadIdx.x + 256 * j) * 2];
+            b[j] = in[(threadIdx.x + 256 * j) * 2 + 1];
+        } else {
+            for (int i = 0; i < 8; ++i) { a[j][i] = (__bf16)1.0f; b[j][i] = (__bf16)0.5f; }
+        }
+    }
+    f32x4 c[4];
+    for (int j = 0; j < 4; ++j)
+        for (int i = 0; i < 4; ++i) c[j][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j], b[j], c[j], 0, 0, 0);
+    }
+    out[blockIdx.x * 256 + threadIdx.x] = c[0][0] + c[1][1] + c[2][2] + c[3][3];
+}
+
 int main() {
     hipDeviceProp_t p;
     CK(hipGetDeviceProperties(&p, 0));
@@ -195,6 +253,20 @@ int main() {
         run_chains<2>(256, dout, e0, e1) || run_chains<4>(256, dout, e0, e1) ||
         run_chains<4>(512, dout, e0, e1))
         return 1;
+    for (int mode = 0; mode < 2; ++mode) {
+        const int iters = 200000;
+        const double flops = 512.0 * 4 * (double)iters * 4 * 16384.0;
+        for (int rep = 0; rep < 3; ++rep) {
+            CK(hipEventRecord(e0));
+            if (mode == 0) mfma16_loop<false><<<512, 256>>>(din, dout, iters);
+            else mfma16_loop<true><<<512, 256>>>(din, dout, iters);
+            CK(hipEventRecord(e1));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+        }
+        printf("mfma_f32_16x16x32_bf16, %s operands, %7.2f ms launch: %.1f TFLOP/s\n",
+               mode ? "random" : "constant", ms, flops / ms / 1e9);
+    }
     {
         int* di;
         CK(hipMalloc(&di, 256 * 512 * sizeof(int)));
@@ -264,6 +336,82 @@ int main() {
         }
         printf("device copy of 62.7 MB, cold: %.1f us per launch = %.1f GB/s (read + write)\n",
                tot / reps * 1e3, (double)win * 16 / (tot / reps) / 1e6);
+    }
+    // ---- the HBM ceiling, from cold: 1 GiB windows rotating through 4 GiB buffers (nothing
+    //      of a window is left in any cache when it comes round again) ---------------------
+    CK(hipFree(a));
+    CK(hipFree(b));
+    {
+        const size_t win_b = (size_t)1 << 30, nwin = 4;
+        uint4 *src, *dst;
+        CK(hipMalloc(&src, win_b * nwin));
+        CK(hipMalloc(&dst, win_b * nwin));
+        CK(hipMemset(src, 3, win_b * nwin));
+        CK(hipMemset(dst, 4, win_b * nwin));
+        const size_t nv = win_b / 16;
+        const int reps = 8;
+        auto report = [&](const char* what, float total_ms, double bytes_per_launch) {
+            printf("%s: %.1f us per launch = %.1f GB/s\n", what, total_ms / reps * 1e3,
+                   bytes_per_launch / (total_ms / reps) / 1e6);
+        };
+        float tot;
+#define TIMED(LABEL, BYTES, LAUNCH)                                      \
+        tot = 0.f;                                                        \
+        for (int rep = 0; rep < reps + 2; ++rep) {                        \
+            const size_t w = (size_t)(rep % nwin) * nv;                   \
+            (void)w;                                                      \
+            CK(hipEventRecord(e0));                                       \
+            LAUNCH;                                                       \
+            CK(hipEventRecord(e1));                                       \
+            CK(hipEventSynchronize(e1));                                  \
+            CK(hipEventElapsedTime(&ms, e0, e1));                         \
+            if (rep >= 2) tot += ms;                                      \
+        }                                                                 \
+        report(LABEL, tot, BYTES);
+        TIMED("cold copy of 1 GiB, hipMemcpyDtoDAsync (read + write)", 2.0 * win_b,
+              CK(hipMemcpyDtoDAsync((hipDeviceptr_t)(dst + w), (hipDeviceptr_t)(src + w), win_b, 0)));
+        TIMED("cold copy of 1 GiB, kernel, 1 vector in flight per thread (read + write)", 2.0 * win_b,
+              (copy_kernel<<<8192, 256>>>(src + w, dst + w, nv)));
+        TIMED("cold copy of 1 GiB, kernel, 4 vectors in flight per thread (read + write)", 2.0 * win_b,
+              (copy_unrolled<4><<<4096, 256>>>(src + w, dst + w, nv)));
+        TIMED("cold copy of 1 GiB, kernel, 8 vectors in flight per thread (read + write)", 2.0 * win_b,
+              (copy_unrolled<8><<<4096, 256>>>(src + w, dst + w, nv)));
+        TIMED("cold copy of 1 GiB, kernel, 8 vectors in flight, one block-round per block (read + write)", 2.0 * win_b,
+              (copy_unrolled<8><<<(unsigned)(nv / (256 * 8)), 256>>>(src + w, dst + w, nv)));
+        TIMED("cold read of 1 GiB, kernel, 1 vector in flight per thread", 1.0 * win_b,
+              (read_kernel<<<2048, 256>>>(src + w, dst, nv)));
+        TIMED("cold read of 1 GiB, kernel, 8 vectors in flight per thread", 1.0 * win_b,
+              (read_unrolled<8><<<4096, 256>>>(src + w, dst, nv)));
+        TIMED("cold write of 1 GiB, kernel", 1.0 * win_b, (fill_kernel<<<8192, 256>>>(dst + w, nv)));
+        // ---- a second read of what was just read: how much of it the Infinity Cache (256 MB,
+        //      memory side) still holds, by size; a 1 GiB read in between evicts everything
+        const size_t sizes_mb[6] = {32, 64, 96, 128, 192, 256};
+        for (int si = 0; si < 6; ++si) {
+            const size_t n = sizes_mb[si] * 1000000 / 16;
+            float t_first = 0.f, t_second = 0.f, t_second_rev = 0.f;
+            for (int rep = 0; rep < 5; ++rep) {
+                read_unrolled<8><<<4096, 256>>>(src + 2 * nv, dst, nv);          // evict
+                CK(hipEventRecord(e0));
+                read_unrolled<8><<<2048, 256>>>(src, dst, n);
+                CK(hipEventRecord(e1));
+                CK(hipEventSynchronize(e1));
+                CK(hipEventElapsedTime(&ms, e0, e1));
+                t_first += ms;
+                CK(hipEventRecord(e0));
+                read_unrolled<8><<<2048, 256>>>(src, dst, n);
+                CK(hipEventRecord(e1));
+                CK(hipEventSynchronize(e1));
+                CK(hipEventElapsedTime(&ms, e0, e1));
+                t_second += ms;
+            }
+            (void)t_second_rev;
+            printf("read of %3zu MB: first %.1f us = %.0f GB/s, again at once %.1f us = %.0f GB/s\n", sizes_mb[si],
+                   t_first / 5 * 1e3, (double)n * 16 / (t_first / 5) / 1e6, t_second / 5 * 1e3,
+                   (double)n * 16 / (t_second / 5) / 1e6);
+        }
+#undef TIMED
+        CK(hipFree(src));
+        CK(hipFree(dst));
     }
     CK(hipDeviceSynchronize());
     return 0;

@@ -201,7 +201,8 @@ def run_rollout(cfg: RolloutConfig, device: str = "cuda", keep_indices: bool = F
 
 def _mass_and_compress(cfg, q_obs, k, v, merged, budget):
     mass = B.flowcache_attention_mass(q_obs, k, merged)
-    kept = B.flowcache_kv_compress(k, v, merged, budget, mass, cfg.pool_k, cfg.lam)
+    # the caller synchronises right after this anyway (timing): check the compaction's status word
+    kept = B.flowcache_kv_compress(k, v, merged, budget, mass, cfg.pool_k, cfg.lam, check_status=True)
     return mass, kept
 
 

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_bench_json_contract():
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "mid", "--steps", "2",
-                          "--warmup", "1", "--cpu-rows", "8"], capture_output=True, text=True, cwd=ROOT)
+                          "--warmup", "1", "--cpu-rows", "8", "--secondary", "none"], capture_output=True, text=True, cwd=ROOT)
     assert res.returncode == 0, res.stderr[-2000:]
     lines = [l for l in res.stdout.strip().splitlines() if l.strip()]
     assert len(lines) == 1
@@ -27,7 +27,13 @@ def test_bench_json_contract():
     assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12 and "traffic" in r
     c = d["cpu_baseline"]
-    assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and isinstance(c["sample"], str)
+    assert c["kind"] == "oracle" and c["cores"] == 1 and c["nproc"] >= 1 and c["value"] > 0
+    assert isinstance(c["sample"], str)
+    names = [x["call"].split()[0] for x in d["calls"]]
+    for n in ("decide", "decide_metric", "gather", "scatter", "mass", "compress", "select", "compact"):
+        assert n in names, n
+    for x in d["calls"]:
+        assert x["ms"] > 0 and abs(x["frac"] - x["achieved"] / x["peak"]) < 1e-12
     assert d["value"] > 0 and d["ms_per_step"] > 0
     assert set(d["stage_ms_alone"]) == {"decide", "scatter", "attend", "mass", "compress"}
     assert d["streams"] == "one" and set(d["stage_ms"]) == {"decide", "scatter", "attend", "mass", "compress"}
@@ -35,10 +41,20 @@ def test_bench_json_contract():
 
 def test_bench_overlap_mode_runs_mass_and_selection_on_a_second_stream():
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "mid", "--steps", "2",
-                          "--warmup", "1", "--no-cpu", "--overlap"], capture_output=True, text=True, cwd=ROOT)
+                          "--warmup", "1", "--no-cpu", "--overlap", "--secondary", "none"], capture_output=True, text=True, cwd=ROOT)
     assert res.returncode == 0, res.stderr[-2000:]
     d = json.loads(res.stdout.strip().splitlines()[-1])
     assert d["streams"].startswith("two") and "compact" in d["stage_ms"] and d["value"] > 0
+
+
+def test_bench_reports_a_second_workload_in_the_same_line():
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "mid", "--steps", "2",
+                          "--warmup", "1", "--no-cpu", "--secondary", "mid"], capture_output=True, text=True,
+                         cwd=ROOT)
+    assert res.returncode == 0, res.stderr[-2000:]
+    d = json.loads(res.stdout.strip().splitlines()[-1])
+    assert "secondary" not in d                     # same workload twice: nothing to add
+    # the default pair is (C3, C2): checked at full size by the round's bench run, not here
 
 
 def test_bench_refuses_more_than_one_gpu():

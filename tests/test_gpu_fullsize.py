@@ -10,6 +10,7 @@ import torch
 from oracle import flowcache_oracle as O
 from paper_2602_10825_amd import binding as B
 from paper_2602_10825_amd import synth
+from tests._checks import assert_mass_close
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 DEV = "cuda"
@@ -103,13 +104,11 @@ def test_full_size_step_matches_oracle(wl, per_chunk, heads):
     q_obs = np.ascontiguousarray(a["q"][A * L_c - W:])
     mass = B.flowcache_attention_mass(B.to_device(q_obs, wl.dtype, DEV), kc, L_k)
     ref_mass = O.attention_mass(q_obs, kc_ref, L_k)
-    m = mass.cpu().numpy().astype(np.float64)
-    assert np.all(m >= 0) and np.allclose(m.sum(1), 1.0, atol=1e-4)
-    assert (np.abs(m - ref_mass).sum(1) / ref_mass.sum(1)).max() <= 1e-2
+    assert_mass_close(mass.cpu().numpy(), ref_mass, wl.dtype, wl.name)
 
     # ---- compression from the same mass bits: kept indices and both caches bit-exact ----
     print("  compression", flush=True)
-    kept = B.flowcache_kv_compress(kc, vc, L_k, wl.budget, mass, wl.pool_k, wl.lam)
+    kept = B.flowcache_kv_compress(kc, vc, L_k, wl.budget, mass, wl.pool_k, wl.lam, check_status=True)
     torch.cuda.synchronize()
     rk, rk_k, rk_v, sc = O.kv_compress(kc_ref, vc_ref, L_k, wl.budget, mass.cpu().numpy(),
                                        wl.pool_k, wl.lam)
@@ -117,3 +116,19 @@ def test_full_size_step_matches_oracle(wl, per_chunk, heads):
     assert all(g == 0.0 or g > 1e-12 for g in gaps), f"ambiguous boundary {gaps}"
     assert np.array_equal(kept.cpu().numpy(), rk)
     assert np.array_equal(B.to_host(kc), rk_k) and np.array_equal(B.to_host(vc), rk_v)
+
+
+def test_frame_level_observation_queries_at_full_key_length():
+    """App. D.2.1's frame-level query granularity: one latent frame of queries (a fifth of a
+    SkyReels-like chunk, 2040 rows = 32 row groups) against all 40800 clean keys of every head,
+    element-wise against the oracle."""
+    wl = synth.C2
+    print(f"frame-level queries: {wl.name}", flush=True)
+    Wf = wl.L_c // 5
+    rng = np.random.default_rng(77)
+    q = synth.to_storage(rng.standard_normal((Wf, wl.H_q, wl.d)).astype(np.float32), "bf16")
+    c = synth.compress_inputs(wl, seed=3, kind="clustered")
+    got = B.flowcache_attention_mass(B.to_device(q, "bf16", DEV), B.to_device(c["k"], "bf16", DEV), wl.L_k)
+    torch.cuda.synchronize()
+    ref = O.attention_mass(q, c["k"], wl.L_k)
+    assert_mass_close(got.cpu().numpy(), ref, "bf16", "frame-level queries")

@@ -5,8 +5,6 @@ host mirror run side by side; at every commit the importance mass emitted by the
 compared with the oracle's by tolerance and then fed to BOTH compressions (shared-mass
 protocol), whose kept-index arrays and caches must agree bit for bit -- so the two sides
 hold identical caches all the way through."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -14,18 +12,17 @@ import torch
 from oracle import flowcache_oracle as O
 from paper_2602_10825_amd import binding as B
 from paper_2602_10825_amd import synth
+from tests._checks import assert_mass_close
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1800)]
 DEV = "cuda"
 
-# MAGI-1-like head shape; the default run keeps the cache at 4 chunks and commits 10, the
-# long run (FLOWCACHE_LONG_ROLLOUT=1) is 64 commits at a 16-chunk budget.
-LONG = os.environ.get("FLOWCACHE_LONG_ROLLOUT", "0") == "1"
-
-
+# A reduced shape first; then the long-rollout stress at the MAGI-1-like layer shape: 64 commits
+# to a cache held at 16 chunks (149 760 tokens; merged length 159 120), heavy-tailed keys with
+# 20 % near-duplicates, kept indices compared at all 48 compressing commits (about 5 minutes).
 @pytest.mark.parametrize("wl,budget_chunks,commits", [
     (synth.MID_BF16, 3, 9),
-    (synth.C3, 16, 64) if LONG else (synth.C3, 4, 10),
+    (synth.C3, 16, 64),
 ])
 def test_commit_sequence_keeps_identical_caches(wl, budget_chunks, commits):
     H, L_c, d, W = wl.H_k, wl.L_c, wl.d, wl.obs_window
@@ -56,9 +53,9 @@ def test_commit_sequence_keeps_identical_caches(wl, budget_chunks, commits):
         mass = B.flowcache_attention_mass(B.to_device(q_obs, "bf16", DEV), k_gpu, merged)
         ref_mass = O.attention_mass(q_obs, k_ref, merged)
         m = mass.cpu().numpy()
-        rel = np.abs(m.astype(np.float64) - ref_mass).sum(1) / ref_mass.sum(1)
-        assert rel.max() <= 1e-2, (commit, rel.max())
-        kept = B.flowcache_kv_compress(k_gpu, v_gpu, merged, budget, mass, wl.pool_k, wl.lam)
+        assert_mass_close(m, ref_mass, "bf16", f"commit {commit}")
+        kept = B.flowcache_kv_compress(k_gpu, v_gpu, merged, budget, mass, wl.pool_k, wl.lam,
+                                       check_status=True)
         torch.cuda.synchronize()
         rk, k_ref, v_ref, sc = O.kv_compress(k_ref, v_ref, merged, budget, m, wl.pool_k, wl.lam)
         gaps = [O.boundary_gap(sc[h], budget) for h in range(H)]

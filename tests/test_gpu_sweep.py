@@ -10,6 +10,7 @@ import torch
 from oracle import flowcache_oracle as O
 from paper_2602_10825_amd import binding as B
 from paper_2602_10825_amd import synth
+from tests._checks import assert_mass_close
 from tests.test_gpu_parity import DEV, check_attend, dev, run_attend, run_compress
 
 pytestmark = pytest.mark.gpu
@@ -65,10 +66,7 @@ def test_attend_and_mass_random_shapes(case):
     if mass_len:
         q_obs = O.observation_rows(q_c, len(rec), wl.L_c, W)
         ref_mass = O.attention_mass(q_obs, kc_ref, mass_len)
-        mass = res["mass"].cpu().numpy().astype(np.float64)
-        assert np.all(mass >= 0) and np.allclose(mass.sum(axis=1), 1.0, atol=1e-4)
-        rel_l1 = np.abs(mass - ref_mass).sum(axis=1) / ref_mass.sum(axis=1)
-        assert rel_l1.max() <= (1e-5 if wl.dtype == "f32" else 1e-2)
+        assert_mass_close(res["mass"].cpu().numpy(), ref_mass, wl.dtype, wl.name)
 
 
 @pytest.mark.parametrize("case", range(16))
