@@ -2,26 +2,23 @@
 //
 // Kernels, all stream-ordered, float64 arithmetic, no floating-point atomics:
 //   key_stats      pass 1 over K: per token 1/max(||k||,1e-12) and k^.k^; per block the
-//                  partial sum of normalised keys                      (HBM-bound)
+//                  partial sum of normalised keys
 //   sum_partials   per head: fixed-order sum of the block partials -> s = sum_i k^_i
-//   mean_sim       pass 2 over K: r_j = (k^_j . s - k^_j . k^_j) / L   (HBM-bound), the
-//                  linear-time form of the diagonal-zeroed column mean of Eq. (11);
-//                  writes e_j = exp(r_j) and block partial sums of e.  (The softmax of
-//                  Eq. (11) is shift-invariant and |r_j| <= 1 + 1/L, so no max is
-//                  subtracted.)
+//   mean_sim       pass 2 over K: r_j = (k^_j . s - k^_j . k^_j) / L, the linear-time form of
+//                  the diagonal-zeroed column mean of Eq. (11); writes e_j = exp(r_j) and
+//                  block partial sums of e.  (The softmax of Eq. (11) is shift-invariant and
+//                  |r_j| <= 1 + 1/L, so no max is subtracted.)
 //   score_keys     Red_j = e_j / sum e (Eq. (11)), max-pooled importance (Eq. (10)), score
 //                  (Eq. (12)) -> order-preserving 64-bit keys, block min / max of the keys
 //   key_hist       histogram of the first 11 bits in which the keys of a head differ
-//   select         per head: radix select of the budget-th largest key, continued from
-//                  that histogram and finished on the few candidates left, in LDS
+//   select         per head: radix select of the budget-th largest key: a few blocks gather
+//                  the chosen bin's keys in parallel, the last one to finish ends the select
+//                  on them in LDS
 //   write_kept     ordered compaction of the kept positions (ties: lower position wins;
-//                  output ascending); a block counts what precedes it by itself
-//   compact_rows   move the kept K and V rows to positions [0, budget) IN PLACE, one pass:
-//                  a block takes a ticket (tile-major, so a head's tiles start in order),
-//                  loads the 64 source rows of its tile into registers, publishes "tile
-//                  read", waits until every lower tile of the head has published (only those
-//                  can still need rows the block is about to overwrite, and they are already
-//                  running, so the wait ends), then stores.
+//                  output ascending); blocks exchange their counts through one word each
+//   compact_rows   move the kept K and V rows to positions [0, budget) IN PLACE, one pass of
+//                  64-row tiles drawn from a ticket counter; a tile stores only after the
+//                  lower tiles that read from its rows have loaded them
 // A 16-lane group owns one token row in the two passes over K (16-byte loads, a full
 // row per group), so a token's values never depend on where it sits in the launch.
 #include "fc_common.hpp"
@@ -116,51 +113,104 @@ __device__ __forceinline__ double group_sum_scatter(double (&v)[16], int u) {
     }
 }
 
-// A group of 16 lanes takes 16 consecutive tokens per round: all 16 row slices are loaded
-// first (16 loads in flight per lane), the norms are all-reduced over the group, and lane u
-// finishes token u (square root, reciprocal, the token's record) -- one token per lane
-// instead of every lane repeating the same float64 work.
-template <typename T, int D>
+// Eight sums over the 16 lanes of a group: lanes u and u + 8 both end with the sum of v[u % 8]
+// (three halving steps as above, then one exchange between the two halves of the group).
+__device__ __forceinline__ double group_sum_scatter8(double (&v)[8], int u) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const bool up = u & 1;
+        const double keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
+        v[i] = keep + __shfl_xor(give, 1, 16);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const bool up = u & 2;
+        const double keep = up ? v[2 * i + 1] : v[2 * i], give = up ? v[2 * i] : v[2 * i + 1];
+        v[i] = keep + __shfl_xor(give, 2, 16);
+    }
+    const bool up = u & 4;
+    const double keep = up ? v[1] : v[0], give = up ? v[0] : v[1];
+    const double half = keep + __shfl_xor(give, 4, 16);
+    // the lower lane's term first on both sides, so both lanes get the same bits
+    const double other = __shfl_xor(half, 8, 16);
+    return (u & 8) ? other + half : half + other;
+}
+
+// The two passes over K.  A group of 16 lanes takes R consecutive tokens per round (R = 16 or
+// 8): all R row slices are requested first, the per-token sums are reduced over the group so
+// that lane u ends with token u's, and lane u finishes token u (square root, reciprocal,
+// exponential) -- one token per lane instead of every lane repeating the same float64 work.
+// Both passes are bound by float64 instruction issue and by the latency of the lane exchanges,
+// not by HBM, so what matters is instructions per element and wavefronts per SIMD: with R = 8
+// the widened rows stay in registers for their second use and the kernel fits four to five
+// wavefronts per SIMD.  Rows past the end of the head re-read its last row (branch-free loads)
+// and are given weight zero.
+template <typename T, int D, int R>
+__device__ __forceinline__ void load_round(typename Slice<T, D>::raw_t (&raw)[R], const T* base,
+                                           int64_t tok_stride, int j0, int L, int u) {
+    const int jb = j0 < L ? j0 : L - 1;         // a round wholly past the end re-reads the last row
+    const int room = L - 1 - jb;                // rows of this round that exist beyond the first
+    const T* rb = base + (int64_t)jb * tok_stride;
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+        raw[i] = Slice<T, D>::load(rb + (int64_t)(i < room ? i : room) * tok_stride, u);
+}
+
+template <int R>
+__device__ __forceinline__ double scatter_sum(double (&v)[R], int u) {
+    if constexpr (R == 16) return group_sum_scatter(v, u);
+    else return group_sum_scatter8(v, u);
+}
+
+template <typename T, int D, int R>
 __global__ __launch_bounds__(kThreads) void key_stats_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
     double2* __restrict__ tokinfo, double* __restrict__ psum) {
     typedef Slice<T, D> S;
     constexpr int EL = S::EL;
+    constexpr bool KEEP = (R == 8);   // the widened rows stay in registers between the two uses
     const int h = blockIdx.y;
     const int g = threadIdx.x / 16, u = threadIdx.x % 16;
     const T* base = k_cache + (int64_t)h * head_stride;
     double acc[EL];
 #pragma unroll
     for (int e = 0; e < EL; ++e) acc[e] = 0.0;
-    for (int j0 = (blockIdx.x * kGroups + g) * 16; j0 < L; j0 += gridDim.x * kGroups * 16) {
-        typename S::raw_t raw[16];
+    const int stride = gridDim.x * kGroups * R;
+    for (int j0 = (blockIdx.x * kGroups + g) * R; j0 < L; j0 += stride) {
+        typename S::raw_t raw[R];
+        load_round<T, D, R>(raw, base, tok_stride, j0, L, u);
+        double xs[KEEP ? R : 1][EL];
+        double part[R];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int j = j0 + i;
-            raw[i] = S::load(base + (int64_t)(j < L ? j : L - 1) * tok_stride, u);
-        }
-        double part[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < R; ++i) {
             double x[EL];
             S::widen(raw[i], x);
             double n2 = 0.0;
 #pragma unroll
             for (int e = 0; e < EL; ++e) n2 = fma(x[e], x[e], n2);
             part[i] = n2;
-        }
-        const double mine = group_sum_scatter(part, u);
-        const double inv_mine = 1.0 / fmax(sqrt(mine), 1e-12);
-        if (j0 + u < L) tokinfo[(int64_t)h * L + j0 + u] = make_double2(inv_mine, (mine * inv_mine) * inv_mine);
+            if constexpr (KEEP) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+                for (int e = 0; e < EL; ++e) xs[i][e] = x[e];
+            }
+        }
+        const double mine = scatter_sum<R>(part, u);
+        const double inv_mine = 1.0 / fmax(sqrt(mine), 1e-12);
+        if (u < R && j0 + u < L) tokinfo[(int64_t)h * L + j0 + u] = make_double2(inv_mine, (mine * inv_mine) * inv_mine);
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
             double inv = __shfl(inv_mine, i, 16);
             inv = (j0 + i < L) ? inv : 0.0;   // rows past the end were re-reads of the last row
-            double x[EL];
-            asm volatile("" : "+v"(raw[i]));   // widen again here rather than keep 16 rows of doubles live
-            S::widen(raw[i], x);
+            if constexpr (KEEP) {
 #pragma unroll
-            for (int e = 0; e < EL; ++e) acc[e] = fma(x[e], inv, acc[e]);
+                for (int e = 0; e < EL; ++e) acc[e] = fma(xs[i][e], inv, acc[e]);
+            } else {
+                double x[EL];
+                asm volatile("" : "+v"(raw[i]));   // widen again here rather than keep R rows of doubles live
+                S::widen(raw[i], x);
+#pragma unroll
+                for (int e = 0; e < EL; ++e) acc[e] = fma(x[e], inv, acc[e]);
+            }
         }
     }
     __shared__ double sh[kGroups][D];
@@ -202,7 +252,9 @@ __global__ __launch_bounds__(1024) void sum_partials_kernel(const double* __rest
     }
 }
 
-template <typename T, int D>
+// Pass 2: r_j = (k^_j . s - k^_j . k^_j) / L for every token, e_j = exp(r_j) and the block's
+// partial sum of e.
+template <typename T, int D, int R>
 __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
     const double2* __restrict__ tokinfo, const double* __restrict__ ssum,
@@ -217,19 +269,15 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     for (int e = 0; e < EL; ++e) s[e] = ssum[h * D + u * EL + e];
     const double dL = (double)L;
     double zsum = 0.0;
-    // 16 consecutive tokens per group and round, as in key_stats; lane u exponentiates token u
-    for (int j0 = (blockIdx.x * kGroups + g) * 16; j0 < L; j0 += gridDim.x * kGroups * 16) {
-        typename S::raw_t raw[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int j = j0 + i;
-            raw[i] = S::load(base + (int64_t)(j < L ? j : L - 1) * tok_stride, u);
-        }
-        const bool have = j0 + u < L;
+    const int stride = gridDim.x * kGroups * R;
+    for (int j0 = (blockIdx.x * kGroups + g) * R; j0 < L; j0 += stride) {
+        typename S::raw_t raw[R];
+        load_round<T, D, R>(raw, base, tok_stride, j0, L, u);
+        const bool have = u < R && j0 + u < L;
         const double2 ti = tokinfo[(int64_t)h * L + (have ? j0 + u : L - 1)];
-        double part[16];
+        double part[R];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < R; ++i) {
             double x[EL];
             S::widen(raw[i], x);
             double dot = 0.0;
@@ -237,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
             for (int e = 0; e < EL; ++e) dot = fma(x[e], s[e], dot);
             part[i] = dot;
         }
-        const double mine = group_sum_scatter(part, u);
+        const double mine = scatter_sum<R>(part, u);
         if (have) {
             const double ej = exp((mine * ti.x - ti.y) / dL);
             e_out[(int64_t)h * L + j0 + u] = ej;
@@ -296,7 +344,7 @@ __global__ __launch_bounds__(kThreads) void score_keys_kernel(
     const double* __restrict__ e_all, const MT* __restrict__ mass_all,
     const double* __restrict__ pz_all, int nblkz, int L, int pool_k, double lambda,
     uint64_t* __restrict__ keys_all, uint64_t* __restrict__ pminmax, uint32_t* __restrict__ hist_all,
-    uint32_t* __restrict__ sync, int ntile) {
+    uint32_t* __restrict__ sync, int ntile, uint32_t* __restrict__ selsync, uint64_t* __restrict__ agg_all) {
     const int h = blockIdx.y, tid = threadIdx.x;
     const double* e = e_all + (int64_t)h * L;
     const MT* mass = mass_all + (int64_t)h * L;
@@ -309,6 +357,8 @@ __global__ __launch_bounds__(kThreads) void score_keys_kernel(
         for (int i = tid; i < ntile; i += kThreads) flags[i] = 0u;
         if (tid == 0) sync[64 * (h + 1)] = 0u;
         if (h == 0 && tid == 0) sync[0] = 0u;
+        if (tid < 3) selsync[h * 64 + tid] = 0u;
+        for (int i = tid; i < (int)gridDim.x; i += kThreads) agg_all[(int64_t)h * gridDim.x + i] = 0ull;
     }
     // Z = sum_j e_j: the block partials of the pass that wrote e, in a fixed order
     double z = 0.0;
@@ -471,11 +521,20 @@ __global__ __launch_bounds__(kThreads) void key_hist_kernel(const uint64_t* __re
         if (hist[i]) atomicAdd(&hist_all[(int64_t)h * kBins + i], hist[i]);
 }
 
-// ---- per head: finish the radix select -> threshold key and the number of its copies kept
+// ---- per head: finish the radix select -> threshold key and the number of its copies kept.
+// A few blocks per head.  Every block reads the first-digit histogram and picks the same bin.
+// If that bin holds at most kCand keys (the usual case), the blocks scan the head's keys in
+// parallel and append the bin's keys to a list in global memory; the block that finishes last
+// (an integer count, nobody waits) pulls the list into LDS and finishes the select there.
+// Otherwise -- many equal or nearly equal scores -- block 0 goes on alone with further
+// histogram passes over global memory.  The list is written and read with agent-scope
+// accesses: its writers may sit on other XCDs, whose L2 this block does not see.
+// selsync[h * 64 + 0] = length of the list, [+1] = blocks done, [+2] = ticket of write_kept.
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const uint64_t* __restrict__ keys_all, const uint64_t* __restrict__ pminmax, int nb2,
-    const uint32_t* __restrict__ hist_all, int L, int budget, uint64_t* __restrict__ sel) {
-    const int h = blockIdx.x;
+    const uint32_t* __restrict__ hist_all, int L, int budget, uint64_t* __restrict__ sel,
+    uint64_t* __restrict__ cand_all, uint32_t* __restrict__ selsync) {
+    const int h = blockIdx.y, part = blockIdx.x, nparts = gridDim.x;
     const int tid = threadIdx.x;
     const uint64_t* keys = keys_all + (int64_t)h * L;
     __shared__ uint64_t shu[kSelThreads / FC_WAVE];
@@ -484,128 +543,176 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __shared__ uint32_t wtot[kSelThreads / FC_WAVE];
     __shared__ uint64_t sh_prefix, sh_thr;
     __shared__ uint32_t sh_need, sh_count, sh_ncand;
+    __shared__ int sh_last;
 
     uint64_t kmin, kmax;
     head_minmax<kSelThreads>(pminmax, h, nb2, shu, kmin, kmax);
-    uint64_t thr;
     uint32_t need = (uint32_t)budget;
     const uint64_t diff = kmin ^ kmax;
-    if (diff == 0) {
-        thr = kmax;   // every score is the same: keep the first `budget` positions
-    } else {
-        int rem = 64 - __clzll((long long)diff);                   // undecided low bits
-        uint64_t prefix = (rem == 64) ? 0ull : (kmax >> rem) << rem;
-        bool in_lds = false, first = true;
-        uint32_t ncand = 0;
-        while (rem > 0) {
-            const int w = in_lds ? (rem < 8 ? rem : 8) : (rem < kDigitBits ? rem : kDigitBits);
-            const int shift = rem - w;
-            const int nb = 1 << w;
-            const uint64_t himask = (rem == 64) ? 0ull : (~0ull << rem);
-            if (first) {   // counted by key_hist_kernel
-                for (int i = tid; i < nb; i += kSelThreads) hist[i] = hist_all[(int64_t)h * kBins + i];
-            } else {
-                for (int i = tid; i < nb; i += kSelThreads) hist[i] = 0;
-                __syncthreads();
-                if (in_lds) {
-                    for (uint32_t i0 = 0; i0 < ncand; i0 += kSelThreads) {
-                        const uint32_t i = i0 + tid;
-                        const uint64_t k = (i < ncand) ? cand[i] : 0ull;
-                        hist_add(hist, i < ncand && (k & himask) == prefix,
-                                 (uint32_t)(k >> shift) & (nb - 1));
-                    }
-                } else {
-                    for (int base = 0; base < L; base += kSelThreads * kUnroll) {
-                        uint64_t kv[kUnroll];
+    if (diff == 0) {   // every score is the same: keep the first `budget` positions
+        if (part == 0 && tid == 0) { sel[2 * h] = kmax; sel[2 * h + 1] = need; }
+        return;
+    }
+    int rem = 64 - __clzll((long long)diff);                   // undecided low bits
+    uint64_t prefix = (rem == 64) ? 0ull : (kmax >> rem) << rem;
+    {   // first digit: counted by key_hist_kernel
+        const int w = rem < kDigitBits ? rem : kDigitBits;
+        const int shift = rem - w;
+        const int nb = 1 << w;
+        for (int i = tid; i < nb; i += kSelThreads) hist[i] = hist_all[(int64_t)h * kBins + i];
+        __syncthreads();
+        pick_bin_parallel(hist, nb, need, wtot, prefix, shift, &sh_prefix, &sh_need, &sh_count);
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+        rem = shift;
+    }
+    bool in_lds = false;
+    uint32_t ncand = 0;
+    uint32_t count = sh_count;        // keys in the bin chosen last
+    if (rem > 0 && count <= (uint32_t)kCand) {
+        uint64_t* cand_g = cand_all + (int64_t)h * kCand;
+        uint32_t* cnt = &selsync[h * 64];
+        const uint64_t hm = ~0ull << rem;
+        const int lane = tid & 63;
+        for (int base = part * kSelThreads * kUnroll; base < L; base += nparts * kSelThreads * kUnroll) {
+            uint64_t kv[kUnroll];
 #pragma unroll
-                        for (int u = 0; u < kUnroll; ++u) {
-                            const int j = base + u * kSelThreads + tid;
-                            kv[u] = (j < L) ? keys[j] : 0ull;
-                        }
-#pragma unroll
-                        for (int u = 0; u < kUnroll; ++u)
-                            hist_add(hist, (kv[u] & himask) == prefix && base + u * kSelThreads + tid < L,
-                                     (uint32_t)(kv[u] >> shift) & (nb - 1));
-                    }
-                }
+            for (int u = 0; u < kUnroll; ++u) {
+                const int j = base + u * kSelThreads + tid;
+                kv[u] = (j < L) ? keys[j] : 0ull;
             }
-            first = false;
-            __syncthreads();
-            if (tid == 0) sh_ncand = 0;
-            pick_bin_parallel(hist, nb, need, wtot, prefix, shift, &sh_prefix, &sh_need, &sh_count);
-            __syncthreads();
-            prefix = sh_prefix;
-            need = sh_need;
-            rem = shift;
-            // few candidates left: pull them into LDS and finish there
-            if (!in_lds && rem > 0 && sh_count <= (uint32_t)kCand) {
-                const uint64_t hm = ~0ull << rem;
-                for (int base = 0; base < L; base += kSelThreads * kUnroll) {
-                    uint64_t kv[kUnroll];
 #pragma unroll
-                    for (int u = 0; u < kUnroll; ++u) {
-                        const int j = base + u * kSelThreads + tid;
-                        kv[u] = (j < L) ? keys[j] : 0ull;
-                    }
-#pragma unroll
-                    for (int u = 0; u < kUnroll; ++u)
-                        list_append(cand, &sh_ncand,
-                                    (kv[u] & hm) == prefix && base + u * kSelThreads + tid < L, kv[u]);
+            for (int u = 0; u < kUnroll; ++u) {
+                const bool take = (kv[u] & hm) == prefix && base + u * kSelThreads + tid < L;
+                const uint64_t m = __ballot(take);
+                if (m == 0) continue;
+                const int leader = __ffsll((long long)m) - 1;
+                uint32_t at = 0;
+                if (lane == leader)
+                    at = __hip_atomic_fetch_add(cnt, (uint32_t)__popcll(m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                at = __shfl(at, leader, FC_WAVE);
+                if (take) {
+                    const uint32_t pos = at + __popcll(m & ((1ull << lane) - 1ull));
+                    if (pos < (uint32_t)kCand)   // cannot be more than the histogram counted
+                        __hip_atomic_store(&cand_g[pos], kv[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
-                __syncthreads();
-                ncand = sh_ncand;
-                in_lds = true;
-            }
-            // one candidate left in the chosen bin: it is the threshold, whatever its low bits
-            if (in_lds && rem > 0 && sh_count == 1u) {
-                const uint64_t hm = ~0ull << rem;
-                for (uint32_t i = tid; i < ncand; i += kSelThreads)
-                    if ((cand[i] & hm) == prefix) sh_thr = cand[i];
-                __syncthreads();
-                prefix = sh_thr;
-                rem = 0;
             }
         }
-        thr = prefix;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this block's part of the list is out
+        __syncthreads();
+        if (tid == 0)
+            sh_last = __hip_atomic_fetch_add(&selsync[h * 64 + 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                      (uint32_t)(nparts - 1);
+        __syncthreads();
+        if (!sh_last) return;
+        ncand = __hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (ncand > (uint32_t)kCand) ncand = kCand;
+        for (uint32_t i = tid; i < ncand; i += kSelThreads)
+            cand[i] = __hip_atomic_load(&cand_g[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        in_lds = true;
+    } else if (part != 0) {
+        return;       // threshold already decided, or too many candidates: block 0 goes on alone
+    }
+    for (;;) {
+        // few candidates left and still in global memory: pull them into LDS and finish there
+        if (!in_lds && rem > 0 && count <= (uint32_t)kCand) {
+            if (tid == 0) sh_ncand = 0;
+            __syncthreads();
+            const uint64_t hm = ~0ull << rem;
+            for (int base = 0; base < L; base += kSelThreads * kUnroll) {
+                uint64_t kv[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int j = base + u * kSelThreads + tid;
+                    kv[u] = (j < L) ? keys[j] : 0ull;
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u)
+                    list_append(cand, &sh_ncand,
+                                (kv[u] & hm) == prefix && base + u * kSelThreads + tid < L, kv[u]);
+            }
+            __syncthreads();
+            ncand = sh_ncand;
+            in_lds = true;
+        }
+        // one candidate left in the chosen bin: it is the threshold, whatever its low bits
+        if (in_lds && rem > 0 && count == 1u) {
+            const uint64_t hm = ~0ull << rem;
+            for (uint32_t i = tid; i < ncand; i += kSelThreads)
+                if ((cand[i] & hm) == prefix) sh_thr = cand[i];
+            __syncthreads();
+            prefix = sh_thr;
+            rem = 0;
+        }
+        if (rem == 0) break;
+        const int w = in_lds ? (rem < 8 ? rem : 8) : (rem < kDigitBits ? rem : kDigitBits);
+        const int shift = rem - w;
+        const int nb = 1 << w;
+        const uint64_t himask = (rem == 64) ? 0ull : (~0ull << rem);
+        for (int i = tid; i < nb; i += kSelThreads) hist[i] = 0;
+        __syncthreads();
+        if (in_lds) {
+            for (uint32_t i0 = 0; i0 < ncand; i0 += kSelThreads) {
+                const uint32_t i = i0 + tid;
+                const uint64_t k = (i < ncand) ? cand[i] : 0ull;
+                hist_add(hist, i < ncand && (k & himask) == prefix, (uint32_t)(k >> shift) & (nb - 1));
+            }
+        } else {
+            for (int base = 0; base < L; base += kSelThreads * kUnroll) {
+                uint64_t kv[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int j = base + u * kSelThreads + tid;
+                    kv[u] = (j < L) ? keys[j] : 0ull;
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u)
+                    hist_add(hist, (kv[u] & himask) == prefix && base + u * kSelThreads + tid < L,
+                             (uint32_t)(kv[u] >> shift) & (nb - 1));
+            }
+        }
+        __syncthreads();
+        pick_bin_parallel(hist, nb, need, wtot, prefix, shift, &sh_prefix, &sh_need, &sh_count);
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+        count = sh_count;
+        rem = shift;
     }
     if (tid == 0) {
-        sel[2 * h] = thr;
+        sel[2 * h] = prefix;
         sel[2 * h + 1] = need;
     }
 }
 
 // ---- ordered compaction of the kept positions: position = #greater before + min(#equal
-//      before, need).  A block first counts the tokens that precede its own 2048.
+//      before, need).  A block (2048 tokens, drawn from the head's ticket counter so that lower
+//      blocks are always already running) publishes how many of its keys lie above and at the
+//      threshold, in one 64-bit word with a valid bit, and then adds up the words of the blocks
+//      below it -- they publish before they look at anyone else's, so every wait ends.
 __global__ __launch_bounds__(kThreads) void write_kept_kernel(const uint64_t* __restrict__ keys_all,
                                                               const uint64_t* __restrict__ sel, int L,
                                                               int budget, int32_t* __restrict__ kept_all,
-                                                              uint32_t* __restrict__ sync, int ntile) {
+                                                              uint32_t* __restrict__ sync, int ntile,
+                                                              uint32_t* __restrict__ selsync,
+                                                              uint64_t* __restrict__ agg_all) {
     const int h = blockIdx.y, tid = threadIdx.x;
     const int wave = tid / FC_WAVE, lane = tid & 63;
     const uint64_t* keys = keys_all + (int64_t)h * L;
     int32_t* kept = kept_all + (int64_t)h * budget;
     int32_t* tile_last = sync_tile_last(sync, gridDim.y, ntile, h);   // for the compaction that follows
+    uint64_t* agg = agg_all + (int64_t)h * gridDim.x;
     const uint64_t thr = sel[2 * h];
     const uint32_t need = (uint32_t)sel[2 * h + 1];
     __shared__ uint32_t wtot[2][kThreads / FC_WAVE];
-    const int first = blockIdx.x * kTokBlk;
-
-    uint32_t ng = 0, ne = 0;
-    for (int base = 0; base < first; base += kThreads * kUnroll) {
-        uint64_t kv[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) kv[u] = keys[base + u * kThreads + tid];   // first % 2048 == 0
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) { ng += kv[u] > thr; ne += kv[u] == thr; }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) { ng += __shfl_xor(ng, o, FC_WAVE); ne += __shfl_xor(ne, o, FC_WAVE); }
-    if (lane == 0) { wtot[0][wave] = ng; wtot[1][wave] = ne; }
+    __shared__ int sh_blk;
+    if (tid == 0)
+        sh_blk = (int)__hip_atomic_fetch_add(&selsync[h * 64 + 2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    uint32_t base_gt = 0, base_eq = 0;
-#pragma unroll
-    for (int w = 0; w < kThreads / FC_WAVE; ++w) { base_gt += wtot[0][w]; base_eq += wtot[1][w]; }
-    __syncthreads();
+    const int blk = sh_blk;
+    const int first = blk * kTokBlk;
 
     const int j0 = first + tid * kItems;   // contiguous items per thread: order = position
     uint32_t fgt = 0, feq = 0;
@@ -629,8 +736,39 @@ __global__ __launch_bounds__(kThreads) void write_kept_kernel(const uint64_t* __
     }
     if (lane == 63) { wtot[0][wave] = sg; wtot[1][wave] = se; }
     __syncthreads();
-    uint32_t gt_before = base_gt + sg - cg, eq_before = base_eq + se - ce;
-    for (int w = 0; w < wave; ++w) { gt_before += wtot[0][w]; eq_before += wtot[1][w]; }
+    uint32_t gt_before = sg - cg, eq_before = se - ce;
+    uint32_t tot_g = 0, tot_e = 0;
+#pragma unroll
+    for (int w = 0; w < kThreads / FC_WAVE; ++w) {
+        if (w < wave) { gt_before += wtot[0][w]; eq_before += wtot[1][w]; }
+        tot_g += wtot[0][w];
+        tot_e += wtot[1][w];
+    }
+    if (tid == 0)
+        __hip_atomic_store(&agg[blk], (1ull << 63) | ((uint64_t)tot_g << 32) | (uint64_t)tot_e, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    // what lies below this block
+    uint32_t ng = 0, ne = 0;
+    bool ok = true;
+    for (int b = tid; b < blk; b += kThreads) {
+        uint64_t v = __hip_atomic_load(&agg[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t spins = 0;
+        while (!(v >> 63)) {
+            if (++spins > kSpinLimit) { ok = false; break; }
+            __builtin_amdgcn_s_sleep(2);
+            v = __hip_atomic_load(&agg[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        ng += (uint32_t)(v >> 32) & 0x7fffffffu;
+        ne += (uint32_t)v;
+    }
+    if (!ok) atomicOr(&sync[0], 2u);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { ng += __shfl_xor(ng, o, FC_WAVE); ne += __shfl_xor(ne, o, FC_WAVE); }
+    __syncthreads();
+    if (lane == 0) { wtot[0][wave] = ng; wtot[1][wave] = ne; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kThreads / FC_WAVE; ++w) { gt_before += wtot[0][w]; eq_before += wtot[1][w]; }
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         const bool g = (fgt >> i) & 1u, e = (feq >> i) & 1u;
@@ -805,14 +943,17 @@ unsigned compact_grid(int ntile, int H) {
 }
 
 struct WsLayout {
-    size_t tokinfo, e, keys, psum, ssum, pz, pminmax, hist, sel, sync, total;
+    size_t tokinfo, e, keys, psum, ssum, pz, pminmax, hist, sel, cand, selsync, agg, sync, total;
     int nblk, nb2, ntile;
 };
 
 WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     WsLayout w;
     int nblk = (L + kGroups * 16 - 1) / (kGroups * 16);   // one round of 16 tokens per group
-    const int cap = 2048 / (H > 0 ? H : 1);
+    // three blocks per compute unit over all heads: the passes run at what the memory system
+    // gives for one large read stream with small per-token side streams, whatever the launch
+    // shape (512 to 4096 blocks were within 3 % of each other), so the partials stay few
+    const int cap = 768 / (H > 0 ? H : 1) > 0 ? 768 / (H > 0 ? H : 1) : 1;
     if (nblk > cap) nblk = cap;
     if (nblk < 1) nblk = 1;
     w.nblk = nblk;
@@ -828,6 +969,9 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     w.pminmax = off; off += fc_align_up((size_t)H * w.nb2 * 16);
     w.hist = off;    off += fc_align_up((size_t)H * kBins * 4);
     w.sel = off;     off += fc_align_up((size_t)H * 16);
+    w.cand = off;    off += fc_align_up((size_t)H * kCand * 8);
+    w.selsync = off; off += fc_align_up((size_t)H * 64 * 4);
+    w.agg = off;     off += fc_align_up((size_t)H * w.nb2 * 8);
     w.ntile = (((budget < L) ? budget : L) + kTileRows - 1) / kTileRows;
     w.sync = off;    off += fc_align_up(sync_words(H, w.ntile) * 4);
     (void)esz;
@@ -862,25 +1006,33 @@ int launch_typed(const FcCompressArgs& a, const MT* mass, hipStream_t s, bool co
     uint64_t* pminmax = reinterpret_cast<uint64_t*>(ws + w.pminmax);
     uint32_t* hist = reinterpret_cast<uint32_t*>(ws + w.hist);
     uint64_t* sel = reinterpret_cast<uint64_t*>(ws + w.sel);
+    uint64_t* cand = reinterpret_cast<uint64_t*>(ws + w.cand);
+    uint32_t* selsync = reinterpret_cast<uint32_t*>(ws + w.selsync);
+    uint64_t* agg = reinterpret_cast<uint64_t*>(ws + w.agg);
     uint32_t* sync = reinterpret_cast<uint32_t*>(ws + w.sync);
     const T* kc = reinterpret_cast<const T*>(a.k_cache);
 
-    key_stats_kernel<T, D><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
-                                                                   a.L_k, tokinfo, psum);
+    // rounds of 8 tokens for two-byte storage (the widened rows stay in registers), of 16 otherwise
+    constexpr int R = sizeof(T) == 2 ? 8 : 16;
+    key_stats_kernel<T, D, R><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
+                                                                      a.L_k, tokinfo, psum);
     FC_LAUNCH_CHECK();
     sum_partials_kernel<D><<<a.H_k, 1024, 0, s>>>(psum, w.nblk, ssum);
     FC_LAUNCH_CHECK();
-    mean_sim_kernel<T, D><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
-                                                                  a.L_k, tokinfo, ssum, e, pz);
+    mean_sim_kernel<T, D, R><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
+                                                                     a.L_k, tokinfo, ssum, e, pz);
     FC_LAUNCH_CHECK();
     score_keys_kernel<MT><<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(e, mass, pz, w.nblk, a.L_k, a.pool_k,
-                                                              a.lambda, keys, pminmax, hist, sync, w.ntile);
+                                                              a.lambda, keys, pminmax, hist, sync, w.ntile, selsync, agg);
     FC_LAUNCH_CHECK();
     key_hist_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, pminmax, a.L_k, hist);
     FC_LAUNCH_CHECK();
-    select_kernel<<<a.H_k, kSelThreads, 0, s>>>(keys, pminmax, w.nb2, hist, a.L_k, a.budget, sel);
+    const int nparts = w.nb2 < 8 ? w.nb2 : 8;     // blocks per head that scan for the candidates
+    select_kernel<<<dim3(nparts, a.H_k), kSelThreads, 0, s>>>(keys, pminmax, w.nb2, hist, a.L_k, a.budget, sel,
+                                                             cand, selsync);
     FC_LAUNCH_CHECK();
-    write_kept_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, sel, a.L_k, a.budget, a.kept, sync, w.ntile);
+    write_kept_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, sel, a.L_k, a.budget, a.kept, sync, w.ntile,
+                                                              selsync, agg);
     FC_LAUNCH_CHECK();
     if (!compact || a.phase == 1) return FC_OK;   // scoring and selection only
     if constexpr (sizeof(T) <= 4) {
