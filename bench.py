@@ -55,7 +55,7 @@ def parse():
     ap.add_argument("--secondary", default="C2", choices=["C2", "C3", "mid", "none"],
                     help="a second workload measured in the same run and reported under 'secondary'")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (cpu_baseline) leg")
-    ap.add_argument("--cpu-rows", type=int, default=48, help="oracle attention rows per chunk")
+    ap.add_argument("--cpu-rows", type=int, default=480, help="oracle attention rows per chunk")
     ap.add_argument("--overlap", action="store_true",
                     help="two streams: mass and selection beside the attention instead of after it")
     ap.add_argument("--qkv", default="normal", choices=["normal", "const"],
@@ -90,7 +90,8 @@ def compress_min_bytes(wl, L_k, budget):
 def cpu_baseline(wl, d, a, rows_per_chunk):
     """Time the fp64 oracle, as it stands, single-threaded, on a bounded sample of the same
     workload: attention on sampled query rows of two heads; the change metric on the full
-    tensors; scoring + selection + compaction of a few heads."""
+    tensors; scoring + selection + compaction of every head (about 10-20 s in all at the
+    MAGI-1-like shape)."""
     from oracle import flowcache_oracle as O
     from threadpoolctl import threadpool_limits
     rec = list(range(wl.A))
@@ -103,7 +104,7 @@ def cpu_baseline(wl, d, a, rows_per_chunk):
     heads = sorted({0, wl.H_q - 1})
     G = wl.H_q // wl.H_k
     kheads = sorted({h // G for h in heads})
-    n_cmp = min(wl.H_k, 4)
+    n_cmp = wl.H_k
     with threadpool_limits(limits=1):
         # the sample: the chosen heads only (the oracle widens whatever it is given to float64)
         kc = O.scatter_kv(a["k_cache"][kheads], a["k_new"][:, kheads], rec, a["active_off"], wl.L_c)

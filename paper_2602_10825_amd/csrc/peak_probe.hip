@@ -198,6 +198,51 @@ __global__ __launch_bounds__(256) void mfma16_loop(const bf16x8* in, float* out,
     out[blockIdx.x * 256 + threadIdx.x] = c[0][0] + c[1][1] + c[2][2] + c[3][3];
 }
 
+// ---- the access patterns of the compression kernels, without their arithmetic --------------
+// (a) out-of-place gather of a sorted subset of 256-byte rows of K and V into dense rows: what
+//     the memory system gives the compaction's traffic when nothing has to wait for anything
+__global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ ks, const uint4* __restrict__ vs,
+                                                   uint4* __restrict__ kd, uint4* __restrict__ vd,
+                                                   const int* __restrict__ idx, int B, long head_stride, int H) {
+    const int h = blockIdx.x % H, tile = blockIdx.x / H;
+    const int lrow = threadIdx.x / 16, lcol = threadIdx.x % 16;
+    const int* id = idx + (long)h * B;
+    int src[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) { const int s = tile * 64 + p * 16 + lrow; src[p] = s < B ? id[s] : 0; }
+    uint4 kr[4], vr[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) { const long a = h * head_stride + (long)src[p] * 16 + lcol; kr[p] = ks[a]; vr[p] = vs[a]; }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int s = tile * 64 + p * 16 + lrow;
+        if (s < B) { const long a = h * head_stride + (long)s * 16 + lcol; kd[a] = kr[p]; vd[a] = vr[p]; }
+    }
+}
+// (b) the scoring passes' pattern: 16 lanes per 256-byte row, 16 rows per round, optionally with
+//     the per-token side streams of the second pass (MODE bit 0: 8 bytes written per token,
+//     bit 1: 16 bytes read per token)
+template <int MODE>
+__global__ __launch_bounds__(256) void rows_pass(const uint4* __restrict__ k, long head_stride, int L, unsigned* out,
+                                                 double* __restrict__ eo, const double2* __restrict__ ti) {
+    const int h = blockIdx.y, g = threadIdx.x / 16, u = threadIdx.x % 16;
+    const uint4* base = k + h * head_stride;
+    unsigned acc = 0;
+    const int stride = gridDim.x * 16 * 16;
+    for (int j0 = (blockIdx.x * 16 + g) * 16; j0 < L; j0 += stride) {
+        uint4 raw[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { int j = j0 + i; j = j < L ? j : L - 1; raw[i] = base[(long)j * 16 + u]; }
+        double2 t = make_double2(0, 0);
+        if ((MODE & 2) && j0 + u < L) t = ti[(long)h * L + j0 + u];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc ^= raw[i].x ^ raw[i].y ^ raw[i].z ^ raw[i].w;
+        if ((MODE & 1) && j0 + u < L) eo[(long)h * L + j0 + u] = (double)acc + t.x + t.y;
+        else if (t.x == 1.2345) acc ^= 1;
+    }
+    if (acc == 0x12345678u) out[0] = acc;
+}
+
 int main() {
     hipDeviceProp_t p;
     CK(hipGetDeviceProperties(&p, 0));
@@ -412,6 +457,57 @@ int main() {
 #undef TIMED
         CK(hipFree(src));
         CK(hipFree(dst));
+    }
+    // ---- the compression kernels' traffic patterns on the MAGI-1-like cache (24 heads x 74880
+    //      rows of 256 bytes, four copies rotated so that nothing is served from a cache) ------
+    {
+        const int H = 24, L = 74880;
+        const size_t rows = (size_t)H * L;
+        uint4* kk[4];
+        for (int i = 0; i < 4; ++i) { CK(hipMalloc(&kk[i], rows * 256)); CK(hipMemset(kk[i], i + 1, rows * 256)); }
+        int* didx;
+        CK(hipMalloc(&didx, rows * 4));
+        double* eo; double2* ti; unsigned* flag;
+        CK(hipMalloc(&eo, rows * 8)); CK(hipMalloc(&ti, rows * 16)); CK(hipMemset(ti, 0, rows * 16)); CK(hipMalloc(&flag, 4));
+        const int reps = 8;
+        for (int mode = 0; mode < 4; ++mode) {
+            float tot = 0.f;
+            for (int r = 0; r < reps + 2; ++r) {
+                CK(hipEventRecord(e0));
+                if (mode == 0) rows_pass<0><<<dim3(32, H), 256>>>(kk[r % 4], (long)L * 16, L, flag, eo, ti);
+                if (mode == 1) rows_pass<1><<<dim3(32, H), 256>>>(kk[r % 4], (long)L * 16, L, flag, eo, ti);
+                if (mode == 2) rows_pass<2><<<dim3(32, H), 256>>>(kk[r % 4], (long)L * 16, L, flag, eo, ti);
+                if (mode == 3) rows_pass<3><<<dim3(32, H), 256>>>(kk[r % 4], (long)L * 16, L, flag, eo, ti);
+                CK(hipEventRecord(e1));
+                CK(hipEventSynchronize(e1));
+                CK(hipEventElapsedTime(&ms, e0, e1));
+                if (r >= 2) tot += ms;
+            }
+            const char* what[4] = {"rows read, nothing else", "rows read + 8 bytes written per row", "rows read + 16 bytes read per row",
+                                   "rows read + 16 bytes read and 8 written per row"};
+            printf("scoring-pass pattern, 460 MB of %s: %.1f us = %.0f GB/s on the row bytes\n", what[mode],
+                   tot / reps * 1e3, (double)rows * 256 / (tot / reps) / 1e6);
+        }
+        // every other row kept (density 0.5), then all rows (density 1.0): K and V, out of place
+        std::vector<int> hidx(rows);
+        for (int dens = 0; dens < 2; ++dens) {
+            const int B = dens == 0 ? L / 2 : L;
+            for (int hh = 0; hh < H; ++hh)
+                for (int i = 0; i < B; ++i) hidx[(size_t)hh * B + i] = dens == 0 ? 2 * i + ((i * 7 + hh) % 3 == 0 ? 1 : 0) : i;
+            CK(hipMemcpy(didx, hidx.data(), (size_t)H * B * 4, hipMemcpyHostToDevice));
+            float tot = 0.f;
+            for (int r = 0; r < reps + 2; ++r) {
+                CK(hipEventRecord(e0));
+                gather_rows<<<H * ((B + 63) / 64), 256>>>(kk[r % 2], kk[2 + r % 2], kk[(r + 1) % 2], kk[2 + (r + 1) % 2], didx, B,
+                                                          (long)L * 16, H);
+                CK(hipEventRecord(e1));
+                CK(hipEventSynchronize(e1));
+                CK(hipEventElapsedTime(&ms, e0, e1));
+                if (r >= 2) tot += ms;
+            }
+            printf("row gather, K and V, %s of the rows kept, out of place: %.1f us = %.0f GB/s (read + write of the kept rows)\n",
+                   dens == 0 ? "half" : "all", tot / reps * 1e3, 4.0 * H * B * 256 / (tot / reps) / 1e6);
+        }
     }
     CK(hipDeviceSynchronize());
     return 0;
