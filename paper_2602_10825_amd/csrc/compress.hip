@@ -3,10 +3,10 @@
 // Kernels, all stream-ordered, float64 arithmetic, no floating-point atomics:
 //   key_stats      pass 1 over K: per token 1/max(||k||,1e-12) and k^.k^; per block the
 //                  partial sum of normalised keys
-//   sum_partials   per head: fixed-order sum of the block partials -> s = sum_i k^_i
-//   mean_sim       pass 2 over K: r_j = (k^_j . s - k^_j . k^_j) / L, the linear-time form of
-//                  the diagonal-zeroed column mean of Eq. (11); writes e_j = exp(r_j) and
-//                  block partial sums of e.  (The softmax of Eq. (11) is shift-invariant and
+//   mean_sim       s = sum_i k^_i from the block partials (fixed order), then pass 2 over K:
+//                  r_j = (k^_j . s - k^_j . k^_j) / L, the linear-time form of the
+//                  diagonal-zeroed column mean of Eq. (11); writes e_j = exp(r_j) and block
+//                  partial sums of e.  (The softmax of Eq. (11) is shift-invariant and
 //                  |r_j| <= 1 + 1/L, so no max is subtracted.)
 //   score_keys     Red_j = e_j / sum e (Eq. (11)), max-pooled importance (Eq. (10)), score
 //                  (Eq. (12)) -> order-preserving 64-bit keys, block min / max of the keys
@@ -225,48 +225,38 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
     }
 }
 
-// s = sum over blocks of the partial sums, in a fixed order: thread (slice, e) adds the
-// partials b = slice, slice + SL, ... ; the SL slice sums are then added in slice order.
-template <int D>
-__global__ __launch_bounds__(1024) void sum_partials_kernel(const double* __restrict__ psum,
-                                                            int nblk, double* __restrict__ ssum) {
-    constexpr int SL = 1024 / D;
-    const int h = blockIdx.x, e = threadIdx.x % D, sl = threadIdx.x / D;
-    const double* p = psum + (int64_t)h * nblk * D + e;
-    double t = 0.0;
-    int b = sl;
-    for (; b + 3 * SL < nblk; b += 4 * SL) {
-        const double v0 = p[(int64_t)b * D], v1 = p[(int64_t)(b + SL) * D];
-        const double v2 = p[(int64_t)(b + 2 * SL) * D], v3 = p[(int64_t)(b + 3 * SL) * D];
-        t += v0; t += v1; t += v2; t += v3;
-    }
-    for (; b < nblk; b += SL) t += p[(int64_t)b * D];
-    __shared__ double sh[SL][D];
-    sh[sl][e] = t;
-    __syncthreads();
-    if (sl == 0) {
-        double tot = 0.0;
-#pragma unroll
-        for (int k = 0; k < SL; ++k) tot += sh[k][e];
-        ssum[h * D + e] = tot;
-    }
-}
-
 // Pass 2: r_j = (k^_j . s - k^_j . k^_j) / L for every token, e_j = exp(r_j) and the block's
-// partial sum of e.
+// partial sum of e.  Every block first adds up the head's few block partials of pass 1 itself,
+// in block order (s = sum_i k^_i; the same bits in every block), which saves a launch.
 template <typename T, int D, int R>
 __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
-    const double2* __restrict__ tokinfo, const double* __restrict__ ssum,
+    const double2* __restrict__ tokinfo, const double* __restrict__ psum, int npart,
     double* __restrict__ e_out, double* __restrict__ pz) {
     typedef Slice<T, D> S;
     constexpr int EL = S::EL;
     const int h = blockIdx.y;
     const int g = threadIdx.x / 16, u = threadIdx.x % 16;
     const T* base = k_cache + (int64_t)h * head_stride;
+    __shared__ double sh_s[D];
+    if (threadIdx.x < D) {
+        const double* p = psum + (int64_t)h * npart * D + threadIdx.x;
+        double t = 0.0;
+        int b = 0;
+        for (; b + 8 <= npart; b += 8) {      // eight loads in flight, added in block order
+            double v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = p[(int64_t)(b + q) * D];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) t += v[q];
+        }
+        for (; b < npart; ++b) t += p[(int64_t)b * D];
+        sh_s[threadIdx.x] = t;
+    }
+    __syncthreads();
     double s[EL];
 #pragma unroll
-    for (int e = 0; e < EL; ++e) s[e] = ssum[h * D + u * EL + e];
+    for (int e = 0; e < EL; ++e) s[e] = sh_s[u * EL + e];
     const double dL = (double)L;
     double zsum = 0.0;
     const int stride = gridDim.x * kGroups * R;
@@ -943,7 +933,7 @@ unsigned compact_grid(int ntile, int H) {
 }
 
 struct WsLayout {
-    size_t tokinfo, e, keys, psum, ssum, pz, pminmax, hist, sel, cand, selsync, agg, sync, total;
+    size_t tokinfo, e, keys, psum, pz, pminmax, hist, sel, cand, selsync, agg, sync, total;
     int nblk, nb2, ntile;
 };
 
@@ -964,7 +954,6 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     w.e = off;       off += fc_align_up((size_t)H * L * 8);
     w.keys = off;    off += fc_align_up((size_t)H * L * 8);
     w.psum = off;    off += fc_align_up((size_t)H * nblk * d * 8);
-    w.ssum = off;    off += fc_align_up((size_t)H * d * 8);
     w.pz = off;      off += fc_align_up((size_t)H * nblk * 8);
     w.pminmax = off; off += fc_align_up((size_t)H * w.nb2 * 16);
     w.hist = off;    off += fc_align_up((size_t)H * kBins * 4);
@@ -1001,7 +990,6 @@ int launch_typed(const FcCompressArgs& a, const MT* mass, hipStream_t s, bool co
     double* e = reinterpret_cast<double*>(ws + w.e);
     uint64_t* keys = reinterpret_cast<uint64_t*>(ws + w.keys);
     double* psum = reinterpret_cast<double*>(ws + w.psum);
-    double* ssum = reinterpret_cast<double*>(ws + w.ssum);
     double* pz = reinterpret_cast<double*>(ws + w.pz);
     uint64_t* pminmax = reinterpret_cast<uint64_t*>(ws + w.pminmax);
     uint32_t* hist = reinterpret_cast<uint32_t*>(ws + w.hist);
@@ -1017,10 +1005,8 @@ int launch_typed(const FcCompressArgs& a, const MT* mass, hipStream_t s, bool co
     key_stats_kernel<T, D, R><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
                                                                       a.L_k, tokinfo, psum);
     FC_LAUNCH_CHECK();
-    sum_partials_kernel<D><<<a.H_k, 1024, 0, s>>>(psum, w.nblk, ssum);
-    FC_LAUNCH_CHECK();
     mean_sim_kernel<T, D, R><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
-                                                                     a.L_k, tokinfo, ssum, e, pz);
+                                                                     a.L_k, tokinfo, psum, w.nblk, e, pz);
     FC_LAUNCH_CHECK();
     score_keys_kernel<MT><<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(e, mass, pz, w.nblk, a.L_k, a.pool_k,
                                                               a.lambda, keys, pminmax, hist, sync, w.ntile, selsync, agg);
