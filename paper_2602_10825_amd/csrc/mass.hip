@@ -6,6 +6,7 @@
 //
 // Two passes over the keys (the softmax normaliser of a row is known only after all keys):
 //   stats  per-row running (max, sum-exp) per block of keys             -> partials
+//   lse    (between them) per row: the partials merged, fixed order     -> log2-sum-exp
 //   cols   per key: sum over rows of exp2(s - lse), fixed order         -> mass
 // bf16: both passes use v_mfma_f32_32x32x16_bf16 on 128-key tiles staged through LDS by
 // coalesced 16-byte loads (the passes are bound by the two reads of K), each in the
@@ -164,7 +165,8 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kTile = 128;            // keys per tile: 4 wavefronts x 32 keys
-constexpr int kTilesPerBlock = 8;
+constexpr int kTilesPerBlock = 8;      // at most
+constexpr int kMinTilesPerBlock = 4;
 constexpr int kSpan = kTile * kTilesPerBlock;
 constexpr int kNT = 256;
 constexpr float kPosBig = 1.0e30f;
@@ -269,7 +271,7 @@ __device__ __forceinline__ void tile_scores_t(const MassSmem<D>& sm, int wave, i
 
 // Pass 1: per observation row, max and sum of exp2 over this block's span of keys.
 template <int D>
-__global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, int nrg, int np,
+__global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, int nrg, int np, int tpb,
                                                               float* __restrict__ pm,
                                                               float* __restrict__ pl) {
     int64_t row0;
@@ -280,9 +282,10 @@ __global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, i
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n = lane & 31, half = lane >> 5;
     const bf16_t* kh = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
-    const int jb = blockIdx.x * kSpan;
+    const int span = tpb * kTile;
+    const int jb = blockIdx.x * span;
     const int left = a.mass_len - jb;
-    const int nt = left >= kSpan ? kTilesPerBlock : (left + kTile - 1) / kTile;
+    const int nt = left >= span ? tpb : (left + kTile - 1) / kTile;
     const float c2 = a.scale * kLog2e;
     // row groups of 64 observation rows, one after the other: the block re-reads its own key
     // span (resident in L2 / Infinity Cache after the first group) instead of the whole K
@@ -290,15 +293,15 @@ __global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, i
     const int w0 = rg * kRowGroup;
     const int nw = (a.W - w0 < kRowGroup) ? a.W - w0 : kRowGroup;
     __syncthreads();
-    stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
     u32x4_native kr[D / 16];
-    fetch_ktile<D>(a, kh, jb, kr);
+    fetch_ktile<D>(a, kh, jb, kr);             // on its way while the rows are staged
+    stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
     float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};   // of row rb*32 + n over this lane's keys
     for (int t = 0; t < nt; ++t) {
         __syncthreads();
         store_ktile<D>(sm.k, kr);
         __syncthreads();
-        fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);   // past the end: clamped, unused
+        if (t + 1 < nt) fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);   // never another block's tile
         f32x16_t st[2];
         tile_scores_t<D>(sm, wave, lane, st);
         const int key0 = jb + t * kTile + wave * 32 + half * 4;   // + (r/4)*8 + r%4
@@ -358,15 +361,58 @@ __global__ __launch_bounds__(kNT, 2) void mass_stats_bf16_kernel(FcMassArgs a, i
     }   // row groups
 }
 
+// Between the passes: log2-sum-exp of every observation row over all keys, from the blocks'
+// partials.  One block per (row group, query head); four lanes per row take every fourth
+// partial (loads batched four deep) and merge in a fixed order.  Padding rows get a huge
+// normaliser: their terms vanish.
+__global__ __launch_bounds__(kNT) void mass_lse_bf16_kernel(const float* __restrict__ pm,
+                                                            const float* __restrict__ pl, int nrg, int np,
+                                                            int W, float* __restrict__ lse2) {
+    const int rg = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    const int w0 = rg * kRowGroup;
+    const int nw = (W - w0 < kRowGroup) ? W - w0 : kRowGroup;
+    const int row = tid >> 2, part = tid & 3;
+    const float* m = pm + (((int64_t)h * nrg + rg) * kRowGroup + row) * np;
+    const float* l = pl + (((int64_t)h * nrg + rg) * kRowGroup + row) * np;
+    float mx = kNegBig, sum = 0.f;
+    for (int i0 = part; i0 < np; i0 += 16) {
+        float mi[4], li[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + 4 * u;
+            mi[u] = i < np ? m[i] : kNegBig;
+            li[u] = i < np ? l[i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float mn = fmaxf(mx, mi[u]);
+            sum = sum * __builtin_amdgcn_exp2f(mx - mn) + li[u] * __builtin_amdgcn_exp2f(mi[u] - mn);
+            mx = mn;
+        }
+    }
+#pragma unroll
+    for (int o = 1; o < 4; o <<= 1) {
+        const float mo = __shfl_xor(mx, o, FC_WAVE), so = __shfl_xor(sum, o, FC_WAVE);
+        const float mn = fmaxf(mx, mo);
+        // the lower lane's term first on both sides, so partners agree bit for bit
+        const float lo = (part & o) ? so * __builtin_amdgcn_exp2f(mo - mn) : sum * __builtin_amdgcn_exp2f(mx - mn);
+        const float hi = (part & o) ? sum * __builtin_amdgcn_exp2f(mx - mn) : so * __builtin_amdgcn_exp2f(mo - mn);
+        sum = lo + hi;
+        mx = mn;
+    }
+    if (part == 0)
+        lse2[((int64_t)h * nrg + rg) * kRowGroup + row] = row < nw ? mx + __builtin_amdgcn_logf(sum) : kPosBig;
+}
+
 template <int D>
-__global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, int nrg, int np,
-                                                             const float* __restrict__ pm,
-                                                             const float* __restrict__ pl) {
+__global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, int nrg, int tpb,
+                                                             const float* __restrict__ lse2) {
     const int hk = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int jb = blockIdx.x * kSpan;
+    const int span = tpb * kTile;
+    const int jb = blockIdx.x * span;
     const int left = a.mass_len - jb;
-    const int nkeys = left >= kSpan ? kSpan : left;
+    const int nkeys = left >= span ? span : left;
     int64_t row0;
     if (!resolve_rows(a, row0)) {
         for (int i = tid; i < nkeys; i += kNT)
@@ -385,46 +431,10 @@ __global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, in
         const int w0 = rg * kRowGroup;
         const int nw = (a.W - w0 < kRowGroup) ? a.W - w0 : kRowGroup;
         __syncthreads();
-        stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
-        {
-            // log2-sum-exp of every row over all keys from the blocks' partials: four lanes per
-            // row take every fourth partial (loads batched four deep), then merge in a fixed order
-            const int row = tid >> 2, part = tid & 3;
-            const float* m = pm + (((int64_t)h * nrg + rg) * kRowGroup + row) * np;
-            const float* l = pl + (((int64_t)h * nrg + rg) * kRowGroup + row) * np;
-            float mx = kNegBig, sum = 0.f;
-            for (int i0 = part; i0 < np; i0 += 16) {
-                float mi[4], li[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + 4 * u;
-                    mi[u] = i < np ? m[i] : kNegBig;
-                    li[u] = i < np ? l[i] : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float mn = fmaxf(mx, mi[u]);
-                    sum = sum * __builtin_amdgcn_exp2f(mx - mn) + li[u] * __builtin_amdgcn_exp2f(mi[u] - mn);
-                    mx = mn;
-                }
-            }
-#pragma unroll
-            for (int o = 1; o < 4; o <<= 1) {
-                const float mo = __shfl_xor(mx, o, FC_WAVE), so = __shfl_xor(sum, o, FC_WAVE);
-                const float mn = fmaxf(mx, mo);
-                // the lower lane's term first on both sides, so partners agree bit for bit
-                const float lo = (part & o) ? so * __builtin_amdgcn_exp2f(mo - mn)
-                                            : sum * __builtin_amdgcn_exp2f(mx - mn);
-                const float hi = (part & o) ? sum * __builtin_amdgcn_exp2f(mx - mn)
-                                            : so * __builtin_amdgcn_exp2f(mo - mn);
-                sum = lo + hi;
-                mx = mn;
-            }
-            // padding rows get a huge normaliser: their terms vanish
-            if (part == 0) sm.lse[row] = row < nw ? mx + __builtin_amdgcn_logf(sum) : kPosBig;
-        }
         u32x4_native kr[D / 16];
-        fetch_ktile<D>(a, kh, jb, kr);
+        fetch_ktile<D>(a, kh, jb, kr);         // on its way while the rows are staged
+        stage_q_bf16<D>(a, row0, w0, nw, h, sm.q);
+        if (tid < kRowGroup) sm.lse[tid] = lse2[((int64_t)h * nrg + rg) * kRowGroup + tid];
         __syncthreads();
         float lr[2][16];
 #pragma unroll
@@ -436,7 +446,7 @@ __global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, in
             __syncthreads();
             store_ktile<D>(sm.k, kr);
             __syncthreads();
-            fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);   // past the end: clamped, unused
+            if (t + 1 < nt) fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);   // never another block's tile
             f32x16_t s[2];
             tile_scores<D>(sm, wave, lane, s);
             float v = 0.f;
@@ -455,15 +465,36 @@ __global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, in
     }
 }
 
+// Tiles per block, 4 to 8: blocks of one launch take about the same time, so they run in rounds
+// of as many blocks as the chip holds (two per compute unit); the span is chosen so that the
+// last round is as full as possible (the MAGI-1-like layer: 3528 blocks of 4 tiles fill 6.9
+// rounds of 512, where 1776 blocks of 8 tiles left the fourth round half empty).
+inline int mass_tiles_per_block(int mass_len, int heads) {
+    const int64_t slots = 512;
+    int best = kTilesPerBlock;
+    double best_eff = -1.0;
+    for (int tpb = kTilesPerBlock; tpb >= kMinTilesPerBlock; --tpb) {
+        const int64_t blocks = (int64_t)heads * ((mass_len + tpb * kTile - 1) / (tpb * kTile));
+        const int64_t rounds = (blocks + slots - 1) / slots;
+        const double eff = (double)blocks / (double)(rounds * slots);
+        if (eff > best_eff + 0.02) { best_eff = eff; best = tpb; }   // longer spans unless clearly fuller
+    }
+    return best;
+}
+
 template <int D>
 int launch_bf16(const FcMassArgs& a, hipStream_t s) {
-    const int np = (a.mass_len + kSpan - 1) / kSpan;
+    const int tpb = mass_tiles_per_block(a.mass_len, a.H_q);
+    const int np = (a.mass_len + tpb * kTile - 1) / (tpb * kTile);
     const int nrg = (a.W + kRowGroup - 1) / kRowGroup;
     float* pm = reinterpret_cast<float*>(a.ws);
     float* pl = pm + (size_t)a.H_q * nrg * kRowGroup * np;
-    mass_stats_bf16_kernel<D><<<dim3(np, a.H_q), kNT, 0, s>>>(a, nrg, np, pm, pl);
+    mass_stats_bf16_kernel<D><<<dim3(np, a.H_q), kNT, 0, s>>>(a, nrg, np, tpb, pm, pl);
     FC_LAUNCH_CHECK();
-    mass_cols_bf16_kernel<D><<<dim3(np, a.H_k), kNT, 0, s>>>(a, nrg, np, pm, pl);
+    float* lse2 = pl + (size_t)a.H_q * nrg * kRowGroup * np;
+    mass_lse_bf16_kernel<<<dim3(nrg, a.H_q), kNT, 0, s>>>(pm, pl, nrg, np, a.W, lse2);
+    FC_LAUNCH_CHECK();
+    mass_cols_bf16_kernel<D><<<dim3(np, a.H_k), kNT, 0, s>>>(a, nrg, tpb, lse2);
     FC_LAUNCH_CHECK();
     return FC_OK;
 }
@@ -496,8 +527,8 @@ size_t fc_mass_workspace(int W, int H_q, int mass_len) {
     const size_t f32 = ((size_t)2 * H_q * kRowGroup * np + (size_t)H_q * kRowGroup) * sizeof(float);
     // bf16 path: all row groups in one launch, a partial per block span of keys
     const size_t nrg = ((size_t)(W > 0 ? W : 1) + kRowGroup - 1) / kRowGroup;
-    const size_t nps = ((size_t)mass_len + kSpan - 1) / kSpan;
-    const size_t bf16 = (size_t)2 * H_q * nrg * kRowGroup * nps * sizeof(float);
+    const size_t nps = ((size_t)mass_len + kMinTilesPerBlock * kTile - 1) / (kMinTilesPerBlock * kTile);
+    const size_t bf16 = ((size_t)2 * H_q * nrg * kRowGroup * nps + (size_t)H_q * nrg * kRowGroup) * sizeof(float);
     return fc_align_up(f32 > bf16 ? f32 : bf16);
 }
 
