@@ -1,9 +1,11 @@
 // KV-cache compression at a chunk commit (Sec. 3.3, Eq. (10)-(12); App. C.1, C.2).
 //
 // Kernels, all stream-ordered, float64 arithmetic, no floating-point atomics:
-//   key_stats      pass 1 over K: per token 1/max(||k||,1e-12) and k^.k^; per block the
-//                  partial sum of normalised keys
+//   key_stats      pass 1 over K: per token 1/max(||k||,1e-12); per block the partial sum of
+//                  normalised keys
 //   mean_sim       s = sum_i k^_i from the block partials (fixed order), then pass 2 over K:
+//                  the token's norm again (same operations, same bits: cheaper than a side
+//                  stream of 16 bytes per token written by pass 1 and read here), then
 //                  r_j = (k^_j . s - k^_j . k^_j) / L, the linear-time form of the
 //                  diagonal-zeroed column mean of Eq. (11); writes e_j = exp(r_j) and block
 //                  partial sums of e.  (The softmax of Eq. (11) is shift-invariant and
@@ -140,11 +142,8 @@ __device__ __forceinline__ double group_sum_scatter8(double (&v)[8], int u) {
 // 8): all R row slices are requested first, the per-token sums are reduced over the group so
 // that lane u ends with token u's, and lane u finishes token u (square root, reciprocal,
 // exponential) -- one token per lane instead of every lane repeating the same float64 work.
-// Both passes are bound by float64 instruction issue and by the latency of the lane exchanges,
-// not by HBM, so what matters is instructions per element and wavefronts per SIMD: with R = 8
-// the widened rows stay in registers for their second use and the kernel fits four to five
-// wavefronts per SIMD.  Rows past the end of the head re-read its last row (branch-free loads)
-// and are given weight zero.
+// With R = 8 the widened rows of pass 1 stay in registers for their second use.  Rows past the
+// end of the head re-read its last row (branch-free loads) and are given weight zero.
 template <typename T, int D, int R>
 __device__ __forceinline__ void load_round(typename Slice<T, D>::raw_t (&raw)[R], const T* base,
                                            int64_t tok_stride, int j0, int L, int u) {
@@ -165,7 +164,7 @@ __device__ __forceinline__ double scatter_sum(double (&v)[R], int u) {
 template <typename T, int D, int R>
 __global__ __launch_bounds__(kThreads) void key_stats_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
-    double2* __restrict__ tokinfo, double* __restrict__ psum) {
+    double* __restrict__ psum) {
     typedef Slice<T, D> S;
     constexpr int EL = S::EL;
     constexpr bool KEEP = (R == 8);   // the widened rows stay in registers between the two uses
@@ -176,9 +175,7 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
 #pragma unroll
     for (int e = 0; e < EL; ++e) acc[e] = 0.0;
     const int stride = gridDim.x * kGroups * R;
-    for (int j0 = (blockIdx.x * kGroups + g) * R; j0 < L; j0 += stride) {
-        typename S::raw_t raw[R];
-        load_round<T, D, R>(raw, base, tok_stride, j0, L, u);
+    auto round = [&](typename S::raw_t (&raw)[R], int j0) {
         double xs[KEEP ? R : 1][EL];
         double part[R];
 #pragma unroll
@@ -196,7 +193,6 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
         }
         const double mine = scatter_sum<R>(part, u);
         const double inv_mine = 1.0 / fmax(sqrt(mine), 1e-12);
-        if (u < R && j0 + u < L) tokinfo[(int64_t)h * L + j0 + u] = make_double2(inv_mine, (mine * inv_mine) * inv_mine);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             double inv = __shfl(inv_mine, i, 16);
@@ -211,6 +207,30 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
 #pragma unroll
                 for (int e = 0; e < EL; ++e) acc[e] = fma(x[e], inv, acc[e]);
             }
+        }
+    };
+    // the rows of the next round are requested before the current round is worked on: with the
+    // two or three wavefronts per SIMD that the registers allow, nothing else hides their latency
+    // (rounds of 16 rows of wider storage would need more registers than a wavefront has)
+    if constexpr (R == 8) {
+        typename S::raw_t ra[R], rb[R];
+        int j0 = (blockIdx.x * kGroups + g) * R;
+        if (j0 < L) load_round<T, D, R>(ra, base, tok_stride, j0, L, u);
+        for (; j0 < L; j0 += 2 * stride) {
+            if (j0 + stride < L) load_round<T, D, R>(rb, base, tok_stride, j0 + stride, L, u);
+            __builtin_amdgcn_sched_barrier(0);
+            round(ra, j0);
+            if (j0 + stride < L) {
+                if (j0 + 2 * stride < L) load_round<T, D, R>(ra, base, tok_stride, j0 + 2 * stride, L, u);
+                __builtin_amdgcn_sched_barrier(0);
+                round(rb, j0 + stride);
+            }
+        }
+    } else {
+        for (int j0 = (blockIdx.x * kGroups + g) * R; j0 < L; j0 += stride) {
+            typename S::raw_t raw[R];
+            load_round<T, D, R>(raw, base, tok_stride, j0, L, u);
+            round(raw, j0);
         }
     }
     __shared__ double sh[kGroups][D];
@@ -231,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
 template <typename T, int D, int R>
 __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
-    const double2* __restrict__ tokinfo, const double* __restrict__ psum, int npart,
+    const double* __restrict__ psum, int npart,
     double* __restrict__ e_out, double* __restrict__ pz) {
     typedef Slice<T, D> S;
     constexpr int EL = S::EL;
@@ -264,19 +284,24 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
         typename S::raw_t raw[R];
         load_round<T, D, R>(raw, base, tok_stride, j0, L, u);
         const bool have = u < R && j0 + u < L;
-        const double2 ti = tokinfo[(int64_t)h * L + (have ? j0 + u : L - 1)];
-        double part[R];
+        double part[R], part2[R];
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             double x[EL];
             S::widen(raw[i], x);
-            double dot = 0.0;
+            double dot = 0.0, n2 = 0.0;
 #pragma unroll
             for (int e = 0; e < EL; ++e) dot = fma(x[e], s[e], dot);
+#pragma unroll
+            for (int e = 0; e < EL; ++e) n2 = fma(x[e], x[e], n2);   // as in pass 1, bit for bit
             part[i] = dot;
+            part2[i] = n2;
         }
         const double mine = scatter_sum<R>(part, u);
+        const double n2 = scatter_sum<R>(part2, u);
         if (have) {
+            const double inv = 1.0 / fmax(sqrt(n2), 1e-12);
+            const double2 ti = make_double2(inv, (n2 * inv) * inv);
             const double ej = exp((mine * ti.x - ti.y) / dL);
             e_out[(int64_t)h * L + j0 + u] = ej;
             zsum += ej;
@@ -933,7 +958,7 @@ unsigned compact_grid(int ntile, int H) {
 }
 
 struct WsLayout {
-    size_t tokinfo, e, keys, psum, pz, pminmax, hist, sel, cand, selsync, agg, sync, total;
+    size_t e, keys, psum, pz, pminmax, hist, sel, cand, selsync, agg, sync, total;
     int nblk, nb2, ntile;
 };
 
@@ -950,7 +975,6 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     w.nb2 = (L + kTokBlk - 1) / kTokBlk;
     const size_t esz = (dtype == FC_BF16) ? 2 : 4;
     size_t off = 0;
-    w.tokinfo = off; off += fc_align_up((size_t)H * L * 16);
     w.e = off;       off += fc_align_up((size_t)H * L * 8);
     w.keys = off;    off += fc_align_up((size_t)H * L * 8);
     w.psum = off;    off += fc_align_up((size_t)H * nblk * d * 8);
@@ -986,7 +1010,6 @@ int launch_typed(const FcCompressArgs& a, const MT* mass, hipStream_t s, bool co
         }
     }
     char* ws = reinterpret_cast<char*>(a.ws);
-    double2* tokinfo = reinterpret_cast<double2*>(ws + w.tokinfo);
     double* e = reinterpret_cast<double*>(ws + w.e);
     uint64_t* keys = reinterpret_cast<uint64_t*>(ws + w.keys);
     double* psum = reinterpret_cast<double*>(ws + w.psum);
@@ -1003,10 +1026,10 @@ int launch_typed(const FcCompressArgs& a, const MT* mass, hipStream_t s, bool co
     // rounds of 8 tokens for two-byte storage (the widened rows stay in registers), of 16 otherwise
     constexpr int R = sizeof(T) == 2 ? 8 : 16;
     key_stats_kernel<T, D, R><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
-                                                                      a.L_k, tokinfo, psum);
+                                                                      a.L_k, psum);
     FC_LAUNCH_CHECK();
     mean_sim_kernel<T, D, R><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
-                                                                     a.L_k, tokinfo, psum, w.nblk, e, pz);
+                                                                     a.L_k, psum, w.nblk, e, pz);
     FC_LAUNCH_CHECK();
     score_keys_kernel<MT><<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(e, mass, pz, w.nblk, a.L_k, a.pool_k,
                                                               a.lambda, keys, pminmax, hist, sync, w.ntile, selsync, agg);
