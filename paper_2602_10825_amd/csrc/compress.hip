@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     double* __restrict__ e_out, double* __restrict__ pz) {
     typedef Slice<T, D> S;
     constexpr int EL = S::EL;
-    const int h = blockIdx.y;
+    const int h = gridDim.y - 1 - blockIdx.y;   // pass 1 read the last heads last: they may still be cached
     const int g = threadIdx.x / 16, u = threadIdx.x % 16;
     const T* base = k_cache + (int64_t)h * head_stride;
     __shared__ double sh_s[D];
