@@ -920,8 +920,11 @@ __global__ __launch_bounds__(kThreads) void compact_rows_kernel(
             const int s = row0 + p * RPP + lrow;
             if (cur.src[p] >= 0) {
                 const int64_t a = (int64_t)s * tok_stride_v + lcol;
-                *reinterpret_cast<u32x4_native*>(kh + a) = kr[p];
-                *reinterpret_cast<u32x4_native*>(vh + a) = vr[p];
+                // streaming stores: written the ordinary way, up to a cache's worth of these rows
+                // stays behind as dirty lines and is written back during whichever kernel runs
+                // next (a following pass over 460 MB of cold keys: 118 us instead of 90)
+                __builtin_nontemporal_store(kr[p], reinterpret_cast<u32x4_native*>(kh + a));
+                __builtin_nontemporal_store(vr[p], reinterpret_cast<u32x4_native*>(vh + a));
             }
         }
         if (!more) break;
