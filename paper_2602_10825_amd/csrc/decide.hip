@@ -182,8 +182,9 @@ __global__ __launch_bounds__(kThreads) void decide_finalize_kernel(
 __global__ __launch_bounds__(kThreads) void gather_chunks_kernel(
     const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t chunk_vecs,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ n_rec) {
-    const int r = blockIdx.y;
-    if (r >= *n_rec) return;
+    const int nr = *n_rec;
+    if ((int)blockIdx.y >= nr) return;
+    const int r = nr - 1 - blockIdx.y;   // the metric pass read the last chunks last: they may still be cached
     const int c = idx[r];
     if ((unsigned)c >= gridDim.y) return;
     const uint4* s = src + (int64_t)c * chunk_vecs;
@@ -197,8 +198,9 @@ __global__ __launch_bounds__(kThreads) void gather_chunks_kernel(
 __global__ __launch_bounds__(kThreads) void gather_chunks_bytes_kernel(
     const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int64_t chunk_bytes,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ n_rec) {
-    const int r = blockIdx.y;
-    if (r >= *n_rec) return;
+    const int nr = *n_rec;
+    if ((int)blockIdx.y >= nr) return;
+    const int r = nr - 1 - blockIdx.y;
     const int c = idx[r];
     if ((unsigned)c >= gridDim.y) return;
     const int64_t stride = (int64_t)gridDim.x * kThreads;

@@ -407,7 +407,7 @@ __global__ __launch_bounds__(kNT) void mass_lse_bf16_kernel(const float* __restr
 template <int D>
 __global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, int nrg, int tpb,
                                                              const float* __restrict__ lse2) {
-    const int hk = blockIdx.y;
+    const int hk = gridDim.y - 1 - blockIdx.y;   // the first pass read the last heads last: they may still be cached
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int span = tpb * kTile;
     const int jb = blockIdx.x * span;
