@@ -176,6 +176,15 @@ __global__ __launch_bounds__(256) void fill_kernel(uint4* __restrict__ d, size_t
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) d[i] = v;
 }
 
+// the same fill with streaming (non-temporal) stores
+__global__ __launch_bounds__(256) void fill_stream_kernel(uint4* __restrict__ d, size_t n) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const size_t stride = (size_t)gridDim.x * 256;
+    const u32x4 v = {1u, 2u, 3u, 4u};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(d + i));
+}
+
 template <bool RANDOM>
 __global__ __launch_bounds__(256) void mfma16_loop(const bf16x8* in, float* out, int iters) {
     typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -247,9 +256,10 @@ int main() {
     hipDeviceProp_t p;
     CK(hipGetDeviceProperties(&p, 0));
     printf("device: %s, %d CUs, %d MHz\n", p.gcnArchName, p.multiProcessorCount, p.clockRate / 1000);
-    hipEvent_t e0, e1;
+    hipEvent_t e0, e1, e2;
     CK(hipEventCreate(&e0));
     CK(hipEventCreate(&e1));
+    CK(hipEventCreate(&e2));
     float ms;
 
     const int n16 = 1024 * 2 * 8;
@@ -487,6 +497,35 @@ int main() {
                                    "rows read + 16 bytes read and 8 written per row"};
             printf("scoring-pass pattern, 460 MB of %s: %.1f us = %.0f GB/s on the row bytes\n", what[mode],
                    tot / reps * 1e3, (double)rows * 256 / (tot / reps) / 1e6);
+        }
+        // What a kernel's stores cost the NEXT kernel: a store kernel ends with up to a cache's
+        // worth of its output still dirty in the L2s and the Infinity Cache; the write-back
+        // then runs during whatever is launched next.  A read pass over 460 MB of cold rows is
+        // timed right after a kernel that stored 460 MB elsewhere (ordinary stores, then
+        // streaming stores), and once more with nothing stored in between.
+        {
+            const size_t nv = rows * 16;   // 16-byte vectors in one copy
+            for (int mode = 0; mode < 3; ++mode) {
+                float t_store = 0.f, t_read = 0.f;
+                for (int r = 0; r < reps + 2; ++r) {
+                    CK(hipEventRecord(e0));
+                    if (mode == 0) fill_kernel<<<8192, 256>>>(kk[(r + 2) % 4], nv);
+                    if (mode == 1) fill_stream_kernel<<<8192, 256>>>(kk[(r + 2) % 4], nv);
+                    if (mode == 2) rows_pass<0><<<dim3(32, H), 256>>>(kk[(r + 2) % 4], (long)L * 16, L, flag, eo, ti);
+                    CK(hipEventRecord(e1));
+                    rows_pass<0><<<dim3(32, H), 256>>>(kk[r % 4], (long)L * 16, L, flag, eo, ti);
+                    CK(hipEventRecord(e2));
+                    CK(hipEventSynchronize(e2));
+                    CK(hipEventElapsedTime(&ms, e0, e1));
+                    if (r >= 2) t_store += ms;
+                    CK(hipEventElapsedTime(&ms, e1, e2));
+                    if (r >= 2) t_read += ms;
+                }
+                const char* what[3] = {"a kernel that stored 460 MB (ordinary stores)", "a kernel that stored 460 MB (streaming stores)",
+                                       "a kernel that only read"};
+                printf("read pass over 460 MB of cold rows right after %s: %.1f us (the kernel before it: %.1f us)\n", what[mode],
+                       t_read / reps * 1e3, t_store / reps * 1e3);
+            }
         }
         // every other row kept (density 0.5), then all rows (density 1.0): K and V, out of place
         std::vector<int> hidx(rows);
