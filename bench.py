@@ -43,6 +43,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak
+# What the chip sustains (peak_probe, profiles/peaks_measured.md): a loop of nothing but bf16
+# MFMAs on random operands; a plain read and a plain copy (read + written bytes) from cold.
+MEASURED_MFMA_TFLOPS = 1370.0
+MEASURED_READ_GBPS = 6100.0
+MEASURED_COPY_GBPS = 5200.0
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attend_hbm_traffic.md")
 
 
@@ -322,10 +327,15 @@ def run_workload(wl, args, K, W, with_cpu, torch, B, synth):
     cmp_bytes = compress_min_bytes(wl, L_k, budget)
     kept_rw = 4 * wl.H_k * budget * wl.d * esz
 
-    def hbm(name, key, nbytes, note=None):
+    def hbm(name, key, nbytes, note=None, read_only=0):
+        """frac: against the datasheet rate.  frac_measured: against the time the same bytes take
+        at the rates a plain read and a plain copy sustain on this chip from cold (peak_probe):
+        `read_only` of the bytes are only read, the rest is read-and-written."""
         g = nbytes / (alone[key] * 1e-3) / 1e9
+        floor_ms = (read_only / MEASURED_READ_GBPS + (nbytes - read_only) / MEASURED_COPY_GBPS) / 1e6
         r = {"call": name, "bound": "hbm", "algorithmic_bytes": int(nbytes), "ms": alone[key],
-             "achieved": g, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": g / PEAK_HBM_GBPS}
+             "achieved": g, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": g / PEAK_HBM_GBPS,
+             "frac_measured": floor_ms / alone[key]}
         if note:
             r["note"] = note
         return r
@@ -333,23 +343,25 @@ def run_workload(wl, args, K, W, with_cpu, torch, B, synth):
     gather_ms = max(alone["decide"] - alone["decide_metric"], 1e-6)
     alone["gather"] = gather_ms
     calls = [
-        hbm("decide (metric + decision + gather)", "decide", 4 * one),
-        hbm("decide_metric (metric + decision, no gather)", "decide_metric", 2 * one),
+        hbm("decide (metric + decision + gather)", "decide", 4 * one, read_only=2 * one),
+        hbm("decide_metric (metric + decision, no gather)", "decide_metric", 2 * one, read_only=2 * one),
         hbm("gather (decide minus decide_metric)", "gather", 2 * one),
         hbm("scatter", "scatter", 2 * 2 * wl.A * wl.L_c * wl.H_k * wl.d * esz),
-        hbm("mass", "mass", k_bytes, "algorithmic bytes = K once; the kernels read K twice"),
-        hbm("compress", "compress", cmp_bytes),
-        hbm("select (scoring + top-B, first half of compress)", "select", cmp_bytes - kept_rw),
+        hbm("mass", "mass", k_bytes, "algorithmic bytes = K once; the kernels read K twice", read_only=k_bytes),
+        hbm("compress", "compress", cmp_bytes, read_only=cmp_bytes - kept_rw),
+        hbm("select (scoring + top-B, first half of compress)", "select", cmp_bytes - kept_rw,
+            read_only=cmp_bytes - kept_rw),
         hbm("compact (second half of compress)", "compact", kept_rw + 4 * wl.H_k * budget),
         hbm("residual_apply (all chunks recomputed: store)", "residual_store", 4 * one),
-        hbm("residual_apply (all chunks reused: apply)", "residual_apply", 3 * one),
-        hbm("uniform_decide (+ gather)", "uniform_decide", 4 * one),
+        hbm("residual_apply (all chunks reused: apply)", "residual_apply", 3 * one, read_only=one),
+        hbm("uniform_decide (+ gather)", "uniform_decide", 4 * one, read_only=2 * one),
     ]
     fl = 2.0 * 2 * wl.d * Wf * wl.H_q * L_k                # two passes of Q K^T
     calls.append({"call": f"attention_mass, frame-level queries (W = {Wf})", "bound": "mfma",
                   "ms": alone["mass_frame_queries"], "algorithmic_flops": fl,
                   "achieved": fl / alone["mass_frame_queries"] / 1e9, "peak": PEAK_BF16_TFLOPS,
-                  "unit": "TFLOP/s", "frac": fl / alone["mass_frame_queries"] / 1e9 / PEAK_BF16_TFLOPS})
+                  "unit": "TFLOP/s", "frac": fl / alone["mass_frame_queries"] / 1e9 / PEAK_BF16_TFLOPS,
+                  "frac_measured": fl / alone["mass_frame_queries"] / 1e9 / MEASURED_MFMA_TFLOPS})
 
     result = {
         "value": flops / (ms_per_step * 1e-3) / 1e12,
@@ -367,6 +379,7 @@ def run_workload(wl, args, K, W, with_cpu, torch, B, synth):
                      "algorithmic_bytes": int(2 * wl.A * wl.L_c * wl.H_q * wl.d * esz
                                               + 2 * wl.H_k * wl.capacity * wl.d * esz),
                      "ms": stage_ms["attend"],
+                     "peak_measured": MEASURED_MFMA_TFLOPS, "frac_measured": att_tflops / MEASURED_MFMA_TFLOPS,
                      "note": "a loop of nothing but bf16 MFMAs on random operands sustains 1330-1410 "
                              "TFLOP/s on this chip (power-limited; profiles/peaks_measured.md)"},
         "kv_compress_GBps": cmp_bytes / (alone["compress"] * 1e-3) / 1e9,

@@ -26,6 +26,7 @@ def test_bench_json_contract():
     r = d["roofline"]
     assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12 and "traffic" in r
+    assert abs(r["frac_measured"] - r["achieved"] / r["peak_measured"]) < 1e-12   # beside the datasheet figure
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] == 1 and c["nproc"] >= 1 and c["value"] > 0
     assert isinstance(c["sample"], str)
@@ -34,6 +35,7 @@ def test_bench_json_contract():
         assert n in names, n
     for x in d["calls"]:
         assert x["ms"] > 0 and abs(x["frac"] - x["achieved"] / x["peak"]) < 1e-12
+        assert x["frac_measured"] > x["frac"]        # the measured rates are below the datasheet's
     assert d["value"] > 0 and d["ms_per_step"] > 0
     assert set(d["stage_ms_alone"]) == {"decide", "scatter", "attend", "mass", "compress"}
     assert d["streams"] == "one" and set(d["stage_ms"]) == {"decide", "scatter", "attend", "mass", "compress"}
