@@ -9,10 +9,13 @@
 //                  r_j = (k^_j . s - k^_j . k^_j) / L, the linear-time form of the
 //                  diagonal-zeroed column mean of Eq. (11); writes e_j = exp(r_j) and block
 //                  partial sums of e.  (The softmax of Eq. (11) is shift-invariant and
-//                  |r_j| <= 1 + 1/L, so no max is subtracted.)
+//                  |r_j| <= 1 + 1/L, so no max is subtracted.)  Also per block the smallest
+//                  and largest e and importance value: the bounds score_keys starts from.
 //   score_keys     Red_j = e_j / sum e (Eq. (11)), max-pooled importance (Eq. (10)), score
-//                  (Eq. (12)) -> order-preserving 64-bit keys, block min / max of the keys
-//   key_hist       histogram of the first 11 bits in which the keys of a head differ
+//                  (Eq. (12)) -> order-preserving 64-bit keys; and the histogram of the first
+//                  11 bits below the bits that all keys of the head share, which it knows
+//                  before it has the keys: the score is monotone in e and in the importance,
+//                  rounding included, so the same operations on their extremes bound it
 //   select         per head: radix select of the budget-th largest key: a few blocks gather
 //                  the chosen bin's keys in parallel, the last one to finish ends the select
 //                  on them in LDS
@@ -248,16 +251,19 @@ __global__ __launch_bounds__(kThreads) void key_stats_kernel(
 // Pass 2: r_j = (k^_j . s - k^_j . k^_j) / L for every token, e_j = exp(r_j) and the block's
 // partial sum of e.  Every block first adds up the head's few block partials of pass 1 itself,
 // in block order (s = sum_i k^_i; the same bits in every block), which saves a launch.
-template <typename T, int D, int R>
+template <typename T, int D, int R, typename MT>
 __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     const T* __restrict__ k_cache, int64_t head_stride, int64_t tok_stride, int L,
     const double* __restrict__ psum, int npart,
-    double* __restrict__ e_out, double* __restrict__ pz) {
+    double* __restrict__ e_out, double* __restrict__ pz, const MT* __restrict__ mass_all,
+    double* __restrict__ pstat, uint32_t* __restrict__ hist_all) {
     typedef Slice<T, D> S;
     constexpr int EL = S::EL;
     const int h = gridDim.y - 1 - blockIdx.y;   // pass 1 read the last heads last: they may still be cached
     const int g = threadIdx.x / 16, u = threadIdx.x % 16;
     const T* base = k_cache + (int64_t)h * head_stride;
+    if (blockIdx.x == 0)   // the first-digit histogram that score_keys adds to
+        for (int i = threadIdx.x; i < kBins; i += kThreads) hist_all[(int64_t)h * kBins + i] = 0u;
     __shared__ double sh_s[D];
     if (threadIdx.x < D) {
         const double* p = psum + (int64_t)h * npart * D + threadIdx.x;
@@ -279,6 +285,24 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
     for (int e = 0; e < EL; ++e) s[e] = sh_s[u * EL + e];
     const double dL = (double)L;
     double zsum = 0.0;
+    // Bounds for score_keys (which needs the range of the scores before it has the scores):
+    // smallest and largest e of this block's tokens and smallest and largest importance of a
+    // slice of the head; `odd` notes a value that is not finite.
+    const double kInf = __longlong_as_double(0x7ff0000000000000LL);
+    double emin = kInf, emax = -kInf, mmin = kInf, mmax = -kInf;
+    bool odd = false;
+    // this block's share of the head's importance values: requested now, looked at after the
+    // pass over the rows, so that their latency is not a prologue in front of it
+    constexpr int MP = 12;
+    const MT* mass = mass_all + (int64_t)h * L;
+    const int mj0 = blockIdx.x * kThreads + threadIdx.x, mstride = gridDim.x * kThreads;
+    MT mv[MP];
+#pragma unroll
+    for (int q = 0; q < MP; ++q) {
+        const int j = mj0 + q * mstride;
+        mv[q] = mass[j < L ? j : L - 1];
+    }
+    __builtin_amdgcn_sched_barrier(0);
     const int stride = gridDim.x * kGroups * R;
     for (int j0 = (blockIdx.x * kGroups + g) * R; j0 < L; j0 += stride) {
         typename S::raw_t raw[R];
@@ -305,16 +329,61 @@ __global__ __launch_bounds__(kThreads) void mean_sim_kernel(
             const double ej = exp((mine * ti.x - ti.y) / dL);
             e_out[(int64_t)h * L + j0 + u] = ej;
             zsum += ej;
+            odd = odd || !(ej - ej == 0.0);
+            emin = ej < emin ? ej : emin;
+            emax = ej > emax ? ej : emax;
         }
     }
+#pragma unroll
+    for (int q = 0; q < MP; ++q) {
+        if (mj0 + q * mstride < L) {
+            const double m = (double)mv[q];
+            odd = odd || !(m - m == 0.0);
+            mmin = m < mmin ? m : mmin;
+            mmax = m > mmax ? m : mmax;
+        }
+    }
+    for (int j = mj0 + MP * mstride; j < L; j += mstride) {   // long heads: the rest
+        const double m = (double)mass[j];
+        odd = odd || !(m - m == 0.0);
+        mmin = m < mmin ? m : mmin;
+        mmax = m > mmax ? m : mmax;
+    }
     __shared__ double shz[kThreads];
+    __shared__ double shb[kThreads / FC_WAVE][4];
+    __shared__ int sh_odd;
+    if (threadIdx.x == 0) sh_odd = 0;
     shz[threadIdx.x] = zsum;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {   // minima and maxima: any order gives the same value
+        emin = fmin(emin, __shfl_xor(emin, o, FC_WAVE));
+        emax = fmax(emax, __shfl_xor(emax, o, FC_WAVE));
+        mmin = fmin(mmin, __shfl_xor(mmin, o, FC_WAVE));
+        mmax = fmax(mmax, __shfl_xor(mmax, o, FC_WAVE));
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        double* b = shb[threadIdx.x / FC_WAVE];
+        b[0] = emin; b[1] = emax; b[2] = mmin; b[3] = mmax;
+    }
+    if (odd) sh_odd = 1;
     __syncthreads();
     if (threadIdx.x < 64) {   // fixed order: four strided terms per lane, then the lanes in order
         double z = (shz[threadIdx.x] + shz[threadIdx.x + 64]) + (shz[threadIdx.x + 128] + shz[threadIdx.x + 192]);
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) z += __shfl_down(z, o, FC_WAVE);
-        if (threadIdx.x == 0) pz[(int64_t)h * gridDim.x + blockIdx.x] = z;
+        if (threadIdx.x == 0) {
+            pz[(int64_t)h * gridDim.x + blockIdx.x] = z;
+            double* st = pstat + ((int64_t)h * gridDim.x + blockIdx.x) * 4;
+            double v[4] = {shb[0][0], shb[0][1], shb[0][2], shb[0][3]};
+            for (int w = 1; w < kThreads / FC_WAVE; ++w) {
+                v[0] = fmin(v[0], shb[w][0]); v[1] = fmax(v[1], shb[w][1]);
+                v[2] = fmin(v[2], shb[w][2]); v[3] = fmax(v[3], shb[w][3]);
+            }
+            // a value that is not finite anywhere in the block: the record says so with a NaN
+            st[0] = sh_odd ? __longlong_as_double(0x7ff8000000000000LL) : v[0];
+            st[1] = v[1]; st[2] = v[2]; st[3] = v[3];
+        }
     }
 }
 
@@ -346,6 +415,22 @@ __device__ __forceinline__ uint64_t block_reduce_u64(uint64_t v, bool want_max, 
     return m;
 }
 
+// Histogram increment that survives skew: the digits most lanes of a wavefront share are
+// counted once per wavefront (up to four rounds of leader election); the rest go one by one.
+__device__ __forceinline__ void hist_add(uint32_t* hist, bool in, uint32_t dgt) {
+    uint64_t act = __ballot(in);
+#pragma unroll 1
+    for (int round = 0; round < 4 && act; ++round) {
+        const int leader = __ffsll((long long)act) - 1;
+        const uint32_t d0 = __shfl(dgt, leader, FC_WAVE);
+        const uint64_t same = __ballot(in && dgt == d0);
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+        in = in && (dgt != d0);
+        act &= ~same;
+    }
+    if (in) atomicAdd(&hist[dgt], 1u);
+}
+
 __device__ __forceinline__ uint64_t score_key(double score) {
     if (score == 0.0) score = 0.0;  // -0 -> +0
     const uint64_t b = (uint64_t)__double_as_longlong(score);
@@ -357,17 +442,19 @@ __device__ __forceinline__ uint64_t score_key(double score) {
 template <typename MT>   // importance as given (float) or pooled over a key group (double)
 __global__ __launch_bounds__(kThreads) void score_keys_kernel(
     const double* __restrict__ e_all, const MT* __restrict__ mass_all,
-    const double* __restrict__ pz_all, int nblkz, int L, int pool_k, double lambda,
-    uint64_t* __restrict__ keys_all, uint64_t* __restrict__ pminmax, uint32_t* __restrict__ hist_all,
-    uint32_t* __restrict__ sync, int ntile, uint32_t* __restrict__ selsync, uint64_t* __restrict__ agg_all) {
+    const double* __restrict__ pz_all, const double* __restrict__ pstat_all, int nblkz, int L, int pool_k,
+    double lambda, uint64_t* __restrict__ keys_all, uint64_t* __restrict__ krange,
+    uint32_t* __restrict__ hist_all, uint32_t* __restrict__ sync, int ntile, uint32_t* __restrict__ selsync,
+    uint64_t* __restrict__ agg_all) {
     const int h = blockIdx.y, tid = threadIdx.x;
     const double* e = e_all + (int64_t)h * L;
     const MT* mass = mass_all + (int64_t)h * L;
     uint64_t* keys = keys_all + (int64_t)h * L;
     __shared__ double shd[kThreads];
-    __shared__ uint64_t shu[kThreads / FC_WAVE];
-    if (blockIdx.x == 0) {   // state later kernels of this call start from: histogram, tile flags
-        for (int i = tid; i < kBins; i += kThreads) hist_all[(int64_t)h * kBins + i] = 0u;
+    __shared__ double sh_bound[4];
+    __shared__ int sh_odd;
+    __shared__ uint32_t hist[kBins];
+    if (blockIdx.x == 0) {   // state later kernels of this call start from: tile flags, tickets
         uint32_t* flags = sync_flags(sync, gridDim.y, ntile, h);
         for (int i = tid; i < ntile; i += kThreads) flags[i] = 0u;
         if (tid == 0) sync[64 * (h + 1)] = 0u;
@@ -379,6 +466,47 @@ __global__ __launch_bounds__(kThreads) void score_keys_kernel(
     double z = 0.0;
     for (int i = tid; i < nblkz; i += kThreads) z += pz_all[(int64_t)h * nblkz + i];
     z = block_sum_fixed<kThreads>(z, shd);
+    // The range of the head's scores, before any score: e and the pooled importance of every
+    // token lie between the head's smallest and largest, and every operation from there to the
+    // score is monotone, rounding included, so the same operations on the extremes bound the
+    // scores from both sides.  All keys of the head then agree in the bits above the first in
+    // which the keys of the two bounds differ; the 11 bits below are counted here.
+    if (tid < FC_WAVE) {
+        const double kInf = __longlong_as_double(0x7ff0000000000000LL);
+        double v[4] = {kInf, -kInf, kInf, -kInf};
+        bool odd = false;
+        for (int i = tid; i < nblkz; i += FC_WAVE) {
+            const double* st = pstat_all + ((int64_t)h * nblkz + i) * 4;
+            odd = odd || (st[0] != st[0]);
+            v[0] = fmin(v[0], st[0]); v[1] = fmax(v[1], st[1]);
+            v[2] = fmin(v[2], st[2]); v[3] = fmax(v[3], st[3]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            v[0] = fmin(v[0], __shfl_xor(v[0], o, FC_WAVE)); v[1] = fmax(v[1], __shfl_xor(v[1], o, FC_WAVE));
+            v[2] = fmin(v[2], __shfl_xor(v[2], o, FC_WAVE)); v[3] = fmax(v[3], __shfl_xor(v[3], o, FC_WAVE));
+        }
+        const bool any_odd = __ballot(odd) != 0ull;
+        if (tid == 0) {
+            sh_bound[0] = v[0]; sh_bound[1] = v[1]; sh_bound[2] = v[2]; sh_bound[3] = v[3];
+            sh_odd = any_odd ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    uint64_t klo = 0ull, khi = ~0ull;   // a value that is not finite somewhere: no common bits assumed
+    if (!sh_odd && z - z == 0.0) {
+        const double a_lo = lambda * sh_bound[2], a_hi = lambda * sh_bound[3];
+        const double b_lo = (1.0 - lambda) * (sh_bound[0] / z), b_hi = (1.0 - lambda) * (sh_bound[1] / z);
+        klo = score_key(a_lo - b_hi);
+        khi = score_key(a_hi - b_lo);
+    }
+    const uint64_t kdiff = klo ^ khi;
+    const int rem = kdiff ? 64 - __clzll((long long)kdiff) : 0;
+    const int wbits = rem < kDigitBits ? rem : kDigitBits;
+    const int shift = rem - wbits;
+    if (blockIdx.x == 0 && tid == 0) { krange[2 * h] = klo; krange[2 * h + 1] = khi; }
+    for (int i = tid; i < kBins; i += kThreads) hist[i] = 0u;
+    __syncthreads();
 
     const int half = pool_k / 2;
     const int j0 = blockIdx.x * kTokBlk;
@@ -402,41 +530,26 @@ __global__ __launch_bounds__(kThreads) void score_keys_kernel(
             }
         }
     }
-    uint64_t kmin = ~0ull, kmax = 0ull;
+    uint64_t kv[kItems];
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         const int j = j0 + i * kThreads + tid;
+        kv[i] = 0ull;
         if (j < L) {
             const double red = ev[i] / z;                    // Eq. (11)
             const double a = lambda * (double)imp[i];
             const double b = (1.0 - lambda) * red;
-            const uint64_t k = score_key(a - b);             // Eq. (12)
-            keys[j] = k;
-            kmin = k < kmin ? k : kmin;
-            kmax = k > kmax ? k : kmax;
+            kv[i] = score_key(a - b);                        // Eq. (12)
+            keys[j] = kv[i];
         }
     }
-    kmin = block_reduce_u64<kThreads>(kmin, false, shu);
-    kmax = block_reduce_u64<kThreads>(kmax, true, shu);
-    if (tid == 0) {
-        pminmax[((int64_t)h * gridDim.x + blockIdx.x) * 2] = kmin;
-        pminmax[((int64_t)h * gridDim.x + blockIdx.x) * 2 + 1] = kmax;
-    }
-}
-
-// min and max key of a head from the block partials (every caller gets the same values)
-template <int NT>
-__device__ __forceinline__ void head_minmax(const uint64_t* __restrict__ pminmax, int h, int nb,
-                                            uint64_t* sh, uint64_t& kmin, uint64_t& kmax) {
-    uint64_t lo = ~0ull, hi = 0ull;
-    for (int i = threadIdx.x; i < nb; i += NT) {
-        const uint64_t a = pminmax[((int64_t)h * nb + i) * 2], b = pminmax[((int64_t)h * nb + i) * 2 + 1];
-        lo = a < lo ? a : lo;
-        hi = b > hi ? b : hi;
-    }
-    kmin = block_reduce_u64<NT>(lo, false, sh);
-    kmax = block_reduce_u64<NT>(hi, true, sh);
+    if (rem == 0) return;   // every score of the head is the same: nothing to count
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+        hist_add(hist, j0 + i * kThreads + tid < L, (uint32_t)(kv[i] >> shift) & ((1u << wbits) - 1u));
     __syncthreads();
+    for (int i = tid; i < kBins; i += kThreads)
+        if (hist[i]) atomicAdd(&hist_all[(int64_t)h * kBins + i], hist[i]);
 }
 
 // From a histogram of `nb` <= 2048 bins (counts of the current candidates by digit), find the
@@ -475,22 +588,6 @@ __device__ __forceinline__ void pick_bin_parallel(const uint32_t* hist, int nb, 
     }
 }
 
-// Histogram increment that survives skew: the digits most lanes of a wavefront share are
-// counted once per wavefront (up to four rounds of leader election); the rest go one by one.
-__device__ __forceinline__ void hist_add(uint32_t* hist, bool in, uint32_t dgt) {
-    uint64_t act = __ballot(in);
-#pragma unroll 1
-    for (int round = 0; round < 4 && act; ++round) {
-        const int leader = __ffsll((long long)act) - 1;
-        const uint32_t d0 = __shfl(dgt, leader, FC_WAVE);
-        const uint64_t same = __ballot(in && dgt == d0);
-        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
-        in = in && (dgt != d0);
-        act &= ~same;
-    }
-    if (in) atomicAdd(&hist[dgt], 1u);
-}
-
 // Append `k` to an LDS list from the lanes with `take`; one counter update per wavefront.
 __device__ __forceinline__ void list_append(uint64_t* list, uint32_t* counter, bool take, uint64_t k) {
     const uint64_t m = __ballot(take);
@@ -503,39 +600,6 @@ __device__ __forceinline__ void list_append(uint64_t* list, uint32_t* counter, b
     if (take) list[base + __popcll(m & ((1ull << lane) - 1ull))] = k;
 }
 
-// ---- first radix pass, parallel: all keys of a head agree above bit `top`; count the
-//      next kDigitBits bits
-__global__ __launch_bounds__(kThreads) void key_hist_kernel(const uint64_t* __restrict__ keys_all,
-                                                            const uint64_t* __restrict__ pminmax,
-                                                            int L, uint32_t* __restrict__ hist_all) {
-    const int h = blockIdx.y, tid = threadIdx.x;
-    const uint64_t* keys = keys_all + (int64_t)h * L;
-    __shared__ uint64_t shu[kThreads / FC_WAVE];
-    __shared__ uint32_t hist[kBins];
-    uint64_t kmin, kmax;
-    head_minmax<kThreads>(pminmax, h, gridDim.x, shu, kmin, kmax);
-    const uint64_t diff = kmin ^ kmax;
-    if (diff == 0) return;   // all scores equal: nothing to count
-    const int rem = 64 - __clzll((long long)diff);
-    const int w = rem < kDigitBits ? rem : kDigitBits;
-    const int shift = rem - w;
-    for (int i = tid; i < kBins; i += kThreads) hist[i] = 0;
-    __syncthreads();
-    const int j0 = blockIdx.x * kTokBlk;
-    uint64_t kv[kItems];
-#pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-        const int j = j0 + i * kThreads + tid;
-        kv[i] = (j < L) ? keys[j] : 0ull;
-    }
-#pragma unroll
-    for (int i = 0; i < kItems; ++i)
-        hist_add(hist, j0 + i * kThreads + tid < L, (uint32_t)(kv[i] >> shift) & ((1u << w) - 1u));
-    __syncthreads();
-    for (int i = tid; i < kBins; i += kThreads)
-        if (hist[i]) atomicAdd(&hist_all[(int64_t)h * kBins + i], hist[i]);
-}
-
 // ---- per head: finish the radix select -> threshold key and the number of its copies kept.
 // A few blocks per head.  Every block reads the first-digit histogram and picks the same bin.
 // If that bin holds at most kCand keys (the usual case), the blocks scan the head's keys in
@@ -546,7 +610,7 @@ __global__ __launch_bounds__(kThreads) void key_hist_kernel(const uint64_t* __re
 // accesses: its writers may sit on other XCDs, whose L2 this block does not see.
 // selsync[h * 64 + 0] = length of the list, [+1] = blocks done, [+2] = ticket of write_kept.
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
-    const uint64_t* __restrict__ keys_all, const uint64_t* __restrict__ pminmax, int nb2,
+    const uint64_t* __restrict__ keys_all, const uint64_t* __restrict__ krange,
     const uint32_t* __restrict__ hist_all, int L, int budget, uint64_t* __restrict__ sel,
     uint64_t* __restrict__ cand_all, uint32_t* __restrict__ selsync) {
     const int h = blockIdx.y, part = blockIdx.x, nparts = gridDim.x;
@@ -560,8 +624,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __shared__ uint32_t sh_need, sh_count, sh_ncand;
     __shared__ int sh_last;
 
-    uint64_t kmin, kmax;
-    head_minmax<kSelThreads>(pminmax, h, nb2, shu, kmin, kmax);
+    const uint64_t kmin = krange[2 * h], kmax = krange[2 * h + 1];   // bounds on the head's keys
     uint32_t need = (uint32_t)budget;
     const uint64_t diff = kmin ^ kmax;
     if (diff == 0) {   // every score is the same: keep the first `budget` positions
@@ -570,7 +633,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
     int rem = 64 - __clzll((long long)diff);                   // undecided low bits
     uint64_t prefix = (rem == 64) ? 0ull : (kmax >> rem) << rem;
-    {   // first digit: counted by key_hist_kernel
+    {   // first digit: counted by score_keys_kernel
         const int w = rem < kDigitBits ? rem : kDigitBits;
         const int shift = rem - w;
         const int nb = 1 << w;
@@ -961,7 +1024,7 @@ unsigned compact_grid(int ntile, int H) {
 }
 
 struct WsLayout {
-    size_t e, keys, psum, pz, pminmax, hist, sel, cand, selsync, agg, sync, total;
+    size_t e, keys, psum, pz, pstat, krange, hist, sel, cand, selsync, agg, sync, total;
     int nblk, nb2, ntile;
 };
 
@@ -982,7 +1045,8 @@ WsLayout layout(int H, int L, int d, int budget, fc_dtype dtype) {
     w.keys = off;    off += fc_align_up((size_t)H * L * 8);
     w.psum = off;    off += fc_align_up((size_t)H * nblk * d * 8);
     w.pz = off;      off += fc_align_up((size_t)H * nblk * 8);
-    w.pminmax = off; off += fc_align_up((size_t)H * w.nb2 * 16);
+    w.pstat = off;   off += fc_align_up((size_t)H * nblk * 32);
+    w.krange = off;  off += fc_align_up((size_t)H * 16);
     w.hist = off;    off += fc_align_up((size_t)H * kBins * 4);
     w.sel = off;     off += fc_align_up((size_t)H * 16);
     w.cand = off;    off += fc_align_up((size_t)H * kCand * 8);
@@ -1017,7 +1081,8 @@ int launch_typed(const FcCompressArgs& a, const MT* mass, hipStream_t s, bool co
     uint64_t* keys = reinterpret_cast<uint64_t*>(ws + w.keys);
     double* psum = reinterpret_cast<double*>(ws + w.psum);
     double* pz = reinterpret_cast<double*>(ws + w.pz);
-    uint64_t* pminmax = reinterpret_cast<uint64_t*>(ws + w.pminmax);
+    double* pstat = reinterpret_cast<double*>(ws + w.pstat);
+    uint64_t* krange = reinterpret_cast<uint64_t*>(ws + w.krange);
     uint32_t* hist = reinterpret_cast<uint32_t*>(ws + w.hist);
     uint64_t* sel = reinterpret_cast<uint64_t*>(ws + w.sel);
     uint64_t* cand = reinterpret_cast<uint64_t*>(ws + w.cand);
@@ -1031,17 +1096,16 @@ int launch_typed(const FcCompressArgs& a, const MT* mass, hipStream_t s, bool co
     key_stats_kernel<T, D, R><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
                                                                       a.L_k, psum);
     FC_LAUNCH_CHECK();
-    mean_sim_kernel<T, D, R><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(kc, a.head_stride, a.tok_stride,
-                                                                     a.L_k, psum, w.nblk, e, pz);
+    mean_sim_kernel<T, D, R, MT><<<dim3(w.nblk, a.H_k), kThreads, 0, s>>>(
+        kc, a.head_stride, a.tok_stride, a.L_k, psum, w.nblk, e, pz, mass, pstat, hist);
     FC_LAUNCH_CHECK();
-    score_keys_kernel<MT><<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(e, mass, pz, w.nblk, a.L_k, a.pool_k,
-                                                              a.lambda, keys, pminmax, hist, sync, w.ntile, selsync, agg);
-    FC_LAUNCH_CHECK();
-    key_hist_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, pminmax, a.L_k, hist);
+    score_keys_kernel<MT><<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(e, mass, pz, pstat, w.nblk, a.L_k, a.pool_k,
+                                                              a.lambda, keys, krange, hist, sync, w.ntile,
+                                                              selsync, agg);
     FC_LAUNCH_CHECK();
     const int nparts = w.nb2 < 8 ? w.nb2 : 8;     // blocks per head that scan for the candidates
-    select_kernel<<<dim3(nparts, a.H_k), kSelThreads, 0, s>>>(keys, pminmax, w.nb2, hist, a.L_k, a.budget, sel,
-                                                             cand, selsync);
+    select_kernel<<<dim3(nparts, a.H_k), kSelThreads, 0, s>>>(keys, krange, hist, a.L_k, a.budget, sel, cand,
+                                                             selsync);
     FC_LAUNCH_CHECK();
     write_kept_kernel<<<dim3(w.nb2, a.H_k), kThreads, 0, s>>>(keys, sel, a.L_k, a.budget, a.kept, sync, w.ntile,
                                                               selsync, agg);

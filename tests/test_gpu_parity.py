@@ -361,6 +361,33 @@ def test_compress_exact_ties_and_bf16_d64():
     assert kept.cpu().numpy()[0].tolist() == list(range(32))
 
 
+@pytest.mark.parametrize("wl", [synth.MID_BF16,
+                                synth.Workload("long", "bf16", 2, 2, 128, 1, 8, 9000, 4000)])   # > 4096 keys in a bin
+def test_compress_with_infinite_importance_entries(wl):
+    """Importance values that are not finite switch the first selection digit from the score
+    bounds to the full key range (the bounds would not hold).  The oracle takes finite scores
+    only, so it gets 1e30 where the kernel gets +inf: either way these tokens (and their pool
+    windows, Eq. (10)) outrank everything else, and the rest of the selection is the same."""
+    c = synth.compress_inputs(wl, seed=21, kind="clustered")
+    where = [(0, 3), (0, 500), (0, 999), (1, 64), (1, 65)]
+    huge = c["mass"].copy()
+    for h, j in where:
+        c["mass"][h, j] = np.inf
+        huge[h, j] = np.float32(1e30)
+    k, v = dev(c["k"], wl.dtype), dev(c["v"], wl.dtype)
+    mass = torch.from_numpy(c["mass"][:, :wl.L_k].copy()).to(DEV)
+    kept = B.flowcache_kv_compress(k, v, wl.L_k, wl.budget, mass, 7, 0.07, check_status=True)
+    torch.cuda.synchronize()
+    rk, rk_k, rk_v, sc = O.kv_compress(c["k"], c["v"], wl.L_k, wl.budget, huge[:, :wl.L_k], 7, 0.07)
+    assert all(O.boundary_gap(sc[h], wl.budget) > 1e-12 for h in range(wl.H_k))
+    got = kept.cpu().numpy()
+    assert np.array_equal(got, rk)
+    assert np.array_equal(B.to_host(k), rk_k) and np.array_equal(B.to_host(v), rk_v)
+    for h, j in where:
+        for jj in range(max(0, j - 3), min(wl.L_k, j + 4)):
+            assert jj in got[h]
+
+
 def test_compress_status_word_is_clear_after_normal_calls():
     wl = synth.MID_BF16
     c = synth.compress_inputs(wl, seed=9)
