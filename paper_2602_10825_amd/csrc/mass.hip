@@ -465,6 +465,272 @@ __global__ __launch_bounds__(kNT, 2) void mass_cols_bf16_kernel(FcMassArgs a, in
     }
 }
 
+// ---- bf16, more than one group of 64 observation rows (frame-level queries, App. D.2.1) ------
+// With many row groups the product S = Q K^T is real matrix work, and the two kernels above would
+// stage every key tile again for every row group.  Here the loop order is: chunks of kNR row
+// groups, inside them the key tiles of the block's span, inside a tile the row groups of the
+// chunk.  A key tile is staged once per chunk and its MFMA fragments stay in registers across the
+// chunk's row groups; the row groups' queries pass through a double buffer in LDS (the next group
+// is on its way from L2 while the current one is multiplied; asking two groups ahead gained
+// nothing), one barrier per (tile, row group).
+// Both passes form S^T = K Q^T (one observation row per lane): pass 1 keeps the running (max,
+// sum) of the chunk's row groups in registers, pass 2 adds exp2(s - lse) over the chunk's row
+// groups per lane and reduces over the 32 rows of the lanes once per tile and chunk.
+constexpr int kNR = 4;
+
+template <int D>
+struct __attribute__((aligned(16))) MassWideSmem {
+    __attribute__((aligned(16))) bf16_t q[2][kRowGroup][D + 8];
+    union __attribute__((aligned(16))) {
+        __attribute__((aligned(16))) bf16_t k[kTile][D + 8];
+        float merge[2][32][17];
+    };
+    float lse[kNR][kRowGroup];
+    float acc[kSpan];
+};
+
+template <int D>
+__device__ __forceinline__ void fetch_q_wide(const FcMassArgs& a, int64_t row0, int rg, int h,
+                                             u32x4_native (&qr)[kRowGroup * (D / 8) / kNT]) {
+    constexpr int PR = D / 8;
+    const int w0 = rg * kRowGroup;
+    const int nw = (a.W - w0 < kRowGroup) ? a.W - w0 : kRowGroup;
+#pragma unroll
+    for (int i = 0; i < kRowGroup * PR / kNT; ++i) {
+        const int p = threadIdx.x + kNT * i;
+        const int w = p / PR, c = p % PR;
+        const int wc = w < nw ? w : 0;     // padding rows: a valid row is read, zeros are stored
+        u32x4_native v = *reinterpret_cast<const u32x4_native*>(
+            (const bf16_t*)a.q_base + ((row0 + w0 + wc) * a.H_q + h) * D + c * 8);
+        if (w >= nw) v = u32x4_native{0u, 0u, 0u, 0u};
+        qr[i] = v;
+    }
+}
+template <int D>
+__device__ __forceinline__ void store_q_wide(bf16_t (*qs)[D + 8], const u32x4_native (&qr)[kRowGroup * (D / 8) / kNT]) {
+    constexpr int PR = D / 8;
+#pragma unroll
+    for (int i = 0; i < kRowGroup * PR / kNT; ++i) {
+        const int p = threadIdx.x + kNT * i;
+        *reinterpret_cast<u32x4_native*>(&qs[p / PR][(p % PR) * 8]) = qr[i];
+    }
+}
+
+// S^T[key][row] of this wavefront's 32 keys (fragments kf, in registers) and the 64 staged rows:
+// st[rb][r] = key (r/4)*8 + (lane/32)*4 + r%4 of the wavefront's 32, row rb*32 + lane%32.
+template <int D>
+__device__ __forceinline__ void scores_t_wide(const bf16x8_t (&kf)[D / 16], const bf16_t (*qs)[D + 8],
+                                              int lane, f32x16_t (&st)[2]) {
+    const int n = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        f32x16_t c = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int kb = 0; kb < D / 16; ++kb) {
+            const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(&qs[rb * 32 + n][kb * 16 + half * 8]);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf, c, 0, 0, 0);
+        }
+        st[rb] = c;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kNT, 2) void mass_stats_wide_kernel(FcMassArgs a, int nrg, int np, int tpb,
+                                                              float* __restrict__ pm,
+                                                              float* __restrict__ pl) {
+    int64_t row0;
+    if (!resolve_rows(a, row0)) return;
+    __shared__ __attribute__((aligned(16))) MassWideSmem<D> sm;
+    const int h = blockIdx.y;
+    const int hk = h / (a.H_q / a.H_k);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 31, half = lane >> 5;
+    const bf16_t* kh = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
+    const int span = tpb * kTile;
+    const int jb = blockIdx.x * span;
+    const int left = a.mass_len - jb;
+    const int nt = left >= span ? tpb : (left + kTile - 1) / kTile;
+    const float c2 = a.scale * kLog2e;
+    for (int rc = 0; rc < nrg; rc += kNR) {
+        const int ncr = nrg - rc < kNR ? nrg - rc : kNR;
+        float m[kNR][2], l[kNR][2];
+#pragma unroll
+        for (int g = 0; g < kNR; ++g) { m[g][0] = m[g][1] = kNegBig; l[g][0] = l[g][1] = 0.f; }
+        u32x4_native kr[D / 16];
+        u32x4_native qr[kRowGroup * (D / 8) / kNT];
+        fetch_ktile<D>(a, kh, jb, kr);
+        fetch_q_wide<D>(a, row0, rc, h, qr);
+        bf16x8_t kf[D / 16];
+        for (int t = 0; t < nt; ++t) {
+            __syncthreads();                       // the last tile's fragments are in registers everywhere
+            store_ktile<D>(sm.k, kr);
+            if (t + 1 < nt) fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);
+            const int key0 = jb + t * kTile + wave * 32 + half * 4;   // + (r/4)*8 + r%4
+            const bool full = key0 - half * 4 + 32 <= a.mass_len;
+#pragma unroll
+            for (int g = 0; g < kNR; ++g) {
+                if (g < ncr) {                     // uniform over the block
+                    const int buf = (t * ncr + g) & 1;
+                    store_q_wide<D>(sm.q[buf], qr);
+                    __syncthreads();
+                    if (g == 0) {
+#pragma unroll
+                        for (int kb = 0; kb < D / 16; ++kb)
+                            kf[kb] = *reinterpret_cast<const bf16x8_t*>(&sm.k[wave * 32 + n][kb * 16 + half * 8]);
+                    }
+                    if (!(t == nt - 1 && g == ncr - 1))     // the next pair's queries, on their way from L2
+                        fetch_q_wide<D>(a, row0, rc + (g + 1) % ncr, h, qr);
+                    f32x16_t st[2];
+                    scores_t_wide<D>(kf, sm.q[buf], lane, st);
+                    if (full) {                    // all 32 keys of this wavefront are real
+#pragma unroll
+                        for (int rb = 0; rb < 2; ++rb) {
+                            float tm = st[rb][0];
+#pragma unroll
+                            for (int r = 1; r < 16; ++r) tm = fmaxf(tm, st[rb][r]);
+                            const float mn = fmaxf(m[g][rb], tm * c2);
+                            float acc = 0.f;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) acc += __builtin_amdgcn_exp2f(fmaf(st[rb][r], c2, -mn));
+                            l[g][rb] = fmaf(l[g][rb], __builtin_amdgcn_exp2f(m[g][rb] - mn), acc);
+                            m[g][rb] = mn;
+                        }
+                    } else {                       // the ragged end of the scored range
+#pragma unroll
+                        for (int rb = 0; rb < 2; ++rb) {
+                            float tm = kNegBig;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                if (key0 + (r >> 2) * 8 + (r & 3) < a.mass_len) tm = fmaxf(tm, st[rb][r] * c2);
+                            const float mn = fmaxf(m[g][rb], tm);
+                            float acc = 0.f;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                if (key0 + (r >> 2) * 8 + (r & 3) < a.mass_len)
+                                    acc += __builtin_amdgcn_exp2f(fmaf(st[rb][r], c2, -mn));
+                            // no real key yet (m and mn both at the floor): keep l = 0
+                            l[g][rb] = (mn > kNegBig) ? fmaf(l[g][rb], __builtin_amdgcn_exp2f(m[g][rb] - mn), acc) : 0.f;
+                            m[g][rb] = mn;
+                        }
+                    }
+                }
+            }
+        }
+        // merge the 8 partials of every row (4 wavefronts x 2 lane halves), in a fixed order
+#pragma unroll
+        for (int g = 0; g < kNR; ++g) {
+            if (g < ncr) {
+                __syncthreads();
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    sm.merge[0][rb * 16 + (n >> 1)][(n & 1) * 8 + wave * 2 + half] = m[g][rb];
+                    sm.merge[1][rb * 16 + (n >> 1)][(n & 1) * 8 + wave * 2 + half] = l[g][rb];
+                }
+                __syncthreads();
+                if (tid < kRowGroup) {
+                    const int q = tid;   // rb*32 + n
+                    const float* mp = &sm.merge[0][(q >> 5) * 16 + ((q & 31) >> 1)][(q & 1) * 8];
+                    const float* lp = &sm.merge[1][(q >> 5) * 16 + ((q & 31) >> 1)][(q & 1) * 8];
+                    float mx = kNegBig;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) mx = fmaxf(mx, mp[i]);
+                    float sum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) sum += lp[i] * __builtin_amdgcn_exp2f(mp[i] - mx);
+                    pm[(((int64_t)h * nrg + rc + g) * kRowGroup + q) * np + blockIdx.x] = mx;
+                    pl[(((int64_t)h * nrg + rc + g) * kRowGroup + q) * np + blockIdx.x] = sum;
+                }
+            }
+        }
+        __syncthreads();     // the merge area is the key tile of the next chunk
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kNT, 2) void mass_cols_wide_kernel(FcMassArgs a, int nrg, int tpb,
+                                                             const float* __restrict__ lse2) {
+    const int hk = gridDim.y - 1 - blockIdx.y;   // the first pass read the last heads last
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 31, half = lane >> 5;
+    const int span = tpb * kTile;
+    const int jb = blockIdx.x * span;
+    const int left = a.mass_len - jb;
+    const int nkeys = left >= span ? span : left;
+    int64_t row0;
+    if (!resolve_rows(a, row0)) {
+        for (int i = tid; i < nkeys; i += kNT)
+            a.mass[(int64_t)hk * a.mass_len + jb + i] = __uint_as_float(0x7fc00000u);
+        return;
+    }
+    __shared__ __attribute__((aligned(16))) MassWideSmem<D> sm;
+    const int G = a.H_q / a.H_k;
+    const bf16_t* kh = (const bf16_t*)a.k_cache + (int64_t)hk * a.head_stride;
+    const int nt = (nkeys + kTile - 1) / kTile;
+    const float c2 = a.scale * kLog2e;
+    for (int i = tid; i < kSpan; i += kNT) sm.acc[i] = 0.f;
+    for (int gq = 0; gq < G; ++gq) {
+        const int h = hk * G + gq;
+        for (int rc = 0; rc < nrg; rc += kNR) {
+            const int ncr = nrg - rc < kNR ? nrg - rc : kNR;
+            __syncthreads();                       // the previous chunk's normalisers are no longer read
+            for (int i = tid; i < ncr * kRowGroup; i += kNT)
+                sm.lse[i / kRowGroup][i % kRowGroup] = lse2[((int64_t)h * nrg + rc) * kRowGroup + i];
+            u32x4_native kr[D / 16];
+            u32x4_native qr[kRowGroup * (D / 8) / kNT];
+            fetch_ktile<D>(a, kh, jb, kr);
+            fetch_q_wide<D>(a, row0, rc, h, qr);
+            bf16x8_t kf[D / 16];
+            for (int t = 0; t < nt; ++t) {
+                __syncthreads();
+                store_ktile<D>(sm.k, kr);
+                if (t + 1 < nt) fetch_ktile<D>(a, kh, jb + (t + 1) * kTile, kr);
+                float ka[16];                      // this lane's rows' share of the 16 keys it sees
+#pragma unroll
+                for (int r = 0; r < 16; ++r) ka[r] = 0.f;
+#pragma unroll
+                for (int g = 0; g < kNR; ++g) {
+                    if (g < ncr) {
+                        const int buf = (t * ncr + g) & 1;
+                        store_q_wide<D>(sm.q[buf], qr);
+                        __syncthreads();
+                        if (g == 0) {
+#pragma unroll
+                            for (int kb = 0; kb < D / 16; ++kb)
+                                kf[kb] = *reinterpret_cast<const bf16x8_t*>(&sm.k[wave * 32 + n][kb * 16 + half * 8]);
+                        }
+                        if (!(t == nt - 1 && g == ncr - 1))
+                            fetch_q_wide<D>(a, row0, rc + (g + 1) % ncr, h, qr);
+                        f32x16_t st[2];
+                        scores_t_wide<D>(kf, sm.q[buf], lane, st);
+#pragma unroll
+                        for (int rb = 0; rb < 2; ++rb) {
+                            const float ls = sm.lse[g][rb * 32 + n];   // padding rows: huge, their terms vanish
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) ka[r] += __builtin_amdgcn_exp2f(fmaf(st[rb][r], c2, -ls));
+                        }
+                    }
+                }
+                // over the 32 rows of the lanes (fixed exchange pattern), then one owner per key
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float v = ka[r];
+#pragma unroll
+                    for (int o = 1; o < 32; o <<= 1) v += __shfl_xor(v, o, FC_WAVE);
+                    ka[r] = v;
+                }
+                if (n == 0) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        sm.acc[t * kTile + wave * 32 + (r >> 2) * 8 + half * 4 + (r & 3)] += ka[r];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const float inv = 1.0f / (float)(a.W * G);
+    for (int i = tid; i < nkeys; i += kNT) a.mass[(int64_t)hk * a.mass_len + jb + i] = sm.acc[i] * inv;
+}
+
 // Tiles per block, 4 to 8: blocks of one launch take about the same time, so they run in rounds
 // of as many blocks as the chip holds (two per compute unit); the span is chosen so that the
 // last round is as full as possible (the MAGI-1-like layer: 3528 blocks of 4 tiles fill 6.9
@@ -489,12 +755,18 @@ int launch_bf16(const FcMassArgs& a, hipStream_t s) {
     const int nrg = (a.W + kRowGroup - 1) / kRowGroup;
     float* pm = reinterpret_cast<float*>(a.ws);
     float* pl = pm + (size_t)a.H_q * nrg * kRowGroup * np;
-    mass_stats_bf16_kernel<D><<<dim3(np, a.H_q), kNT, 0, s>>>(a, nrg, np, tpb, pm, pl);
-    FC_LAUNCH_CHECK();
     float* lse2 = pl + (size_t)a.H_q * nrg * kRowGroup * np;
+    if (nrg > 1)
+        mass_stats_wide_kernel<D><<<dim3(np, a.H_q), kNT, 0, s>>>(a, nrg, np, tpb, pm, pl);
+    else
+        mass_stats_bf16_kernel<D><<<dim3(np, a.H_q), kNT, 0, s>>>(a, nrg, np, tpb, pm, pl);
+    FC_LAUNCH_CHECK();
     mass_lse_bf16_kernel<<<dim3(nrg, a.H_q), kNT, 0, s>>>(pm, pl, nrg, np, a.W, lse2);
     FC_LAUNCH_CHECK();
-    mass_cols_bf16_kernel<D><<<dim3(np, a.H_k), kNT, 0, s>>>(a, nrg, tpb, lse2);
+    if (nrg > 1)
+        mass_cols_wide_kernel<D><<<dim3(np, a.H_k), kNT, 0, s>>>(a, nrg, tpb, lse2);
+    else
+        mass_cols_bf16_kernel<D><<<dim3(np, a.H_k), kNT, 0, s>>>(a, nrg, tpb, lse2);
     FC_LAUNCH_CHECK();
     return FC_OK;
 }
